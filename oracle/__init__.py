@@ -1,0 +1,150 @@
+"""ctypes front end of the CPU oracle (``emc2o.c``).
+
+TEST INFRASTRUCTURE ONLY.  Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline``
+leg of ``bench.py`` may import this package; the product (``paper_2507_04123_amd``) never does and
+this package never imports the product's HIP binding.
+
+Every function takes and returns numpy arrays on the host.  Floating point: fp64 accumulation with
+one final rounding to fp32, except the voxel cell index, which is defined in IEEE fp32.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "emc2o.c")
+_LIB = os.path.join(_HERE, "libemc2o.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared",
+               "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    c_i64, c_i32, c_f, vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_float, ctypes.c_void_p
+    lib.emc2o_set_threads.argtypes = [ctypes.c_int]
+    lib.emc2o_get_threads.restype = ctypes.c_int
+    lib.emc2o_max_threads.restype = ctypes.c_int
+    lib.emc2o_voxelize.restype = c_i64
+    lib.emc2o_voxelize.argtypes = [vp, vp, c_i64, c_i32, vp, vp, vp, c_i32, c_f, c_f, c_i64, vp, vp, vp]
+    lib.emc2o_build_kmap.restype = c_i64
+    lib.emc2o_build_kmap.argtypes = [c_i32, vp, c_i64, vp, c_i32, c_i64, vp, vp, vp]
+    lib.emc2o_spconv.restype = c_i64
+    lib.emc2o_spconv.argtypes = [vp, c_i64, vp, vp, vp, c_i32, vp, c_i64, c_i64, c_i32, c_i32, vp]
+    lib.emc2o_project_gather.restype = c_i32
+    lib.emc2o_project_gather.argtypes = [vp, c_i32, c_i64, vp, vp, c_i32, c_i32, c_i32, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _chk(rc: int, what: str) -> int:
+    if rc < 0:
+        raise RuntimeError(f"oracle {what} failed: code {rc}")
+    return rc
+
+
+def set_threads(n: int) -> None:
+    _load().emc2o_set_threads(int(n))
+
+
+def max_threads() -> int:
+    return int(_load().emc2o_max_threads())
+
+
+def voxelize(points: np.ndarray, batch: Optional[np.ndarray], lo: Sequence[float], vs: Sequence[float],
+             grid: Sequence[int], n_batch: int = 1, r2_min: float = 0.0, r2_max: float = float("inf"),
+             capacity: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """points[P][F>=4] fp32 -> (coords[V][4] i32 (b,z,y,x) ascending key, means[V][4] f32, counts[V] i32)."""
+    lib = _load()
+    points = np.ascontiguousarray(points, dtype=np.float32)
+    n, stride = points.shape if points.ndim == 2 else (0, 4)
+    if batch is not None:
+        batch = np.ascontiguousarray(batch, dtype=np.int32)
+        assert batch.shape == (n,)
+    cap = int(capacity if capacity is not None else max(n, 1))
+    coords = np.empty((cap, 4), np.int32)
+    feats = np.empty((cap, 4), np.float32)
+    counts = np.empty((cap,), np.int32)
+    lo_a = np.asarray(lo, np.float32)
+    vs_a = np.asarray(vs, np.float32)
+    g_a = np.asarray(grid, np.int32)
+    v = _chk(lib.emc2o_voxelize(_p(points), _p(batch), n, stride, _p(lo_a), _p(vs_a), _p(g_a), int(n_batch),
+                                float(np.float32(r2_min)), float(np.float32(r2_max)), cap, _p(coords),
+                                _p(feats), _p(counts)), "voxelize")
+    return coords[:v].copy(), feats[:v].copy(), counts[:v].copy()
+
+
+def build_kmap(kind: int, in_coords: np.ndarray, grid_in: Sequence[int], n_batch: int = 1,
+               capacity_out: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray, Tuple[int, int, int]]:
+    """-> (out_coords[Vout][4], nbr[27][Vout] i32 with -1 = absent, grid_out)."""
+    lib = _load()
+    in_coords = np.ascontiguousarray(in_coords, dtype=np.int32).reshape(-1, 4)
+    n_in = in_coords.shape[0]
+    g_in = np.asarray(grid_in, np.int32)
+    if capacity_out is None:
+        gout = g_in if kind == 0 else (g_in - 1) // 2 + 1
+        capacity_out = n_in if kind == 0 else int(min(8 * n_in, int(np.prod(gout.astype(np.int64))) * n_batch))
+    cap = max(int(capacity_out), 1)
+    out_coords = np.empty((cap, 4), np.int32)
+    nbr = np.empty((27, cap), np.int32)
+    g_out = np.zeros(3, np.int32)
+    n_out = _chk(lib.emc2o_build_kmap(int(kind), _p(in_coords), n_in, _p(g_in), int(n_batch), cap,
+                                      _p(out_coords), _p(nbr), _p(g_out)), "build_kmap")
+    return out_coords[:n_out].copy(), np.ascontiguousarray(nbr[:, :n_out]), tuple(int(g) for g in g_out)
+
+
+def spconv(x: np.ndarray, w: np.ndarray, scale: Optional[np.ndarray], shift: Optional[np.ndarray],
+           epilogue: int, nbr: np.ndarray, return_macs: bool = False):
+    """x[Vin][Cin] f32, w[27][Cin][Cout] f32, nbr[27][Vout] -> y[Vout][Cout] f32 (fp64 accumulation)."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+    assert w.ndim == 3 and w.shape[0] == 27 and nbr.ndim == 2 and nbr.shape[0] == 27
+    n_in, cin = x.shape
+    cout = w.shape[2]
+    assert w.shape[1] == cin
+    n_out = nbr.shape[1]
+    if scale is not None:
+        scale = np.ascontiguousarray(scale, dtype=np.float32)
+        shift = np.ascontiguousarray(shift, dtype=np.float32)
+    y = np.empty((n_out, cout), np.float32)
+    macs = _chk(lib.emc2o_spconv(_p(x), n_in, _p(w), _p(scale), _p(shift), int(epilogue), _p(nbr),
+                                 max(n_out, 0), n_out, cin, cout, _p(y)), "spconv")
+    return (y, macs) if return_macs else y
+
+
+def project_gather(points: np.ndarray, pmat: np.ndarray, img: np.ndarray, want_uv: bool = False):
+    """points[P][F>=3] f32, pmat[12] f32, img[H][W][C] (any float; up-cast to f32) -> (g[P][C] f32, valid[P] u8[, uv f64])."""
+    lib = _load()
+    points = np.ascontiguousarray(points, dtype=np.float32)
+    pmat = np.ascontiguousarray(pmat, dtype=np.float32).reshape(12)
+    img32 = np.ascontiguousarray(img.astype(np.float32))
+    h, wd, c = img32.shape
+    n, stride = points.shape
+    out = np.empty((n, c), np.float32)
+    valid = np.empty((n,), np.uint8)
+    uv = np.empty((n, 2), np.float64) if want_uv else None
+    _chk(lib.emc2o_project_gather(_p(points), stride, n, _p(pmat), _p(img32), h, wd, c, _p(out), _p(valid),
+                                  _p(uv)), "project_gather")
+    return (out, valid, uv) if want_uv else (out, valid)

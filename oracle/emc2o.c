@@ -1,0 +1,367 @@
+/*
+ * CPU oracle for the EMC2 LiDAR hot path.  TEST INFRASTRUCTURE ONLY: tests, the smoke check and the
+ * bench's cpu_baseline leg may call this; the product path never does.  It shares no code, header,
+ * table or helper with the HIP library.
+ *
+ * Plain, slow, obviously-correct definitions:
+ *   - voxelization (paper Sec. 2 "process point clouds via voxelization", Sec. 3.1 data bridge,
+ *     Sec. 3.5 configurable pool size): sort points by linear cell key, one run per voxel, mean of
+ *     the run in fp64;
+ *   - kernel map for the 27 offsets of a 3x3x3 sparse conv (Sec. 3.5 "computing nonzero voxels
+ *     only"; Sec. 3.6 index search): sorted key list + binary search;
+ *   - sparse conv (Sec. 3.5, O(N x C_v)): per offset, nested loops, fp64 accumulation, then the
+ *     folded-BN affine + ReLU epilogue (Sec. 3.6 graph fusion) in fp64, rounded once to fp32;
+ *   - point -> image projection with bilinear gather and zero fill for unmatched points
+ *     (Sec. 3.1 / Fig. 5 caption), fp64.
+ *
+ * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
+ * defined by IEEE fp32 subtract, divide, floor).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define EMC2O_ERR_ARG (-1)
+#define EMC2O_ERR_CAPACITY (-2)
+#define EMC2O_ERR_NOMEM (-3)
+
+static int g_threads = 1;
+
+void emc2o_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+
+int emc2o_get_threads(void) { return g_threads; }
+
+int emc2o_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* voxelization                                                                                */
+/* ------------------------------------------------------------------------------------------- */
+
+typedef struct {
+  uint64_t key;
+  int64_t idx;
+} keyed_t;
+
+static int cmp_keyed(const void* a, const void* b) {
+  const keyed_t* p = (const keyed_t*)a;
+  const keyed_t* q = (const keyed_t*)b;
+  if (p->key != q->key) return p->key < q->key ? -1 : 1;
+  if (p->idx != q->idx) return p->idx < q->idx ? -1 : 1;
+  return 0;
+}
+
+/* Cell index along one axis: fp32 subtract, fp32 true division, floor.  Returns -1 if outside. */
+static int cell_of(float p, float lo, float vs, int g) {
+  volatile float d = p - lo; /* volatile: keep each op a separately rounded fp32 op */
+  volatile float t = d / vs;
+  float tt = t;
+  if (!(tt >= 0.0f) || !(tt < (float)g)) return -1; /* also rejects NaN and +-inf */
+  return (int)floorf(tt);
+}
+
+/*
+ * points: [n][stride_f] fp32, columns 0..3 = x, y, z, intensity.  batch: [n] or NULL (=> 0).
+ * Outputs in ascending key order, key = ((b*Gz + z)*Gy + y)*Gx + x:
+ *   coords[v] = (b, z, y, x), feats[v] = mean (x, y, z, intensity) over all points of the voxel
+ *   (fp64 sum, one rounding to fp32), counts[v] = number of points.
+ * Returns the number of voxels, or a negative error.
+ */
+int64_t emc2o_voxelize(const float* points, const int32_t* batch, int64_t n, int32_t stride_f,
+                       const float lo[3], const float vs[3], const int32_t grid[3], int32_t n_batch,
+                       float r2_min, float r2_max, int64_t capacity, int32_t* coords, float* feats,
+                       int32_t* counts) {
+  if (n < 0 || stride_f < 4 || n_batch < 1 || grid[0] < 1 || grid[1] < 1 || grid[2] < 1)
+    return EMC2O_ERR_ARG;
+  keyed_t* ks = (keyed_t*)malloc(sizeof(keyed_t) * (size_t)(n > 0 ? n : 1));
+  if (!ks) return EMC2O_ERR_NOMEM;
+  int64_t m = 0;
+  const uint64_t gx = (uint64_t)grid[0], gy = (uint64_t)grid[1], gz = (uint64_t)grid[2];
+  for (int64_t i = 0; i < n; ++i) {
+    const float* p = points + i * stride_f;
+    int b = batch ? batch[i] : 0;
+    if (b < 0 || b >= n_batch) continue;
+    if (!isfinite(p[3])) continue;
+    int cx = cell_of(p[0], lo[0], vs[0], grid[0]);
+    int cy = cell_of(p[1], lo[1], vs[1], grid[1]);
+    int cz = cell_of(p[2], lo[2], vs[2], grid[2]);
+    if (cx < 0 || cy < 0 || cz < 0) continue;
+    volatile float xx = p[0] * p[0];
+    volatile float yy = p[1] * p[1];
+    volatile float r2 = xx + yy;
+    float rr = r2;
+    if (!(rr >= r2_min) || !(rr < r2_max)) continue;
+    ks[m].key = (((uint64_t)b * gz + (uint64_t)cz) * gy + (uint64_t)cy) * gx + (uint64_t)cx;
+    ks[m].idx = i;
+    ++m;
+  }
+  qsort(ks, (size_t)m, sizeof(keyed_t), cmp_keyed);
+  int64_t v = 0;
+  int64_t i = 0;
+  while (i < m) {
+    int64_t j = i;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    while (j < m && ks[j].key == ks[i].key) {
+      const float* p = points + ks[j].idx * stride_f;
+      for (int c = 0; c < 4; ++c) s[c] += (double)p[c];
+      ++j;
+    }
+    if (v >= capacity) {
+      free(ks);
+      return EMC2O_ERR_CAPACITY;
+    }
+    uint64_t k = ks[i].key;
+    coords[4 * v + 3] = (int32_t)(k % gx);
+    k /= gx;
+    coords[4 * v + 2] = (int32_t)(k % gy);
+    k /= gy;
+    coords[4 * v + 1] = (int32_t)(k % gz);
+    k /= gz;
+    coords[4 * v + 0] = (int32_t)k;
+    double cnt = (double)(j - i);
+    for (int c = 0; c < 4; ++c) feats[4 * v + c] = (float)(s[c] / cnt);
+    counts[v] = (int32_t)(j - i);
+    ++v;
+    i = j;
+  }
+  free(ks);
+  return v;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* kernel maps                                                                                 */
+/* ------------------------------------------------------------------------------------------- */
+
+static int cmp_u64(const void* a, const void* b) {
+  uint64_t p = *(const uint64_t*)a, q = *(const uint64_t*)b;
+  return p < q ? -1 : (p > q ? 1 : 0);
+}
+
+static uint64_t key_of(int64_t b, int64_t z, int64_t y, int64_t x, const int32_t g[3]) {
+  return (((uint64_t)b * (uint64_t)g[2] + (uint64_t)z) * (uint64_t)g[1] + (uint64_t)y) *
+             (uint64_t)g[0] + (uint64_t)x;
+}
+
+/* Index of `key` in the ascending array keys[n], or -1. */
+static int64_t find_key(const uint64_t* keys, int64_t n, uint64_t key) {
+  int64_t lo = 0, hi = n;
+  while (lo < hi) {
+    int64_t mid = lo + (hi - lo) / 2;
+    if (keys[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return (lo < n && keys[lo] == key) ? lo : -1;
+}
+
+/*
+ * kind 0 = submanifold (s=1, p=1): output sites = input sites, same order.
+ * kind 1 = strided   (s=2, p=1): output o active iff some tap reads an active input; outputs in
+ *          ascending key order on grid_out = (G-1)/2+1.
+ * Tap k = (kz*3 + ky)*3 + kx reads input i = o*s - 1 + (kx, ky, kz) (cross-correlation).
+ * nbr[k*capacity_out + o] = index of that input among in_coords, or -1.
+ * in_coords must be ascending in key (what emc2o_voxelize / this function produce).
+ * Returns n_out or a negative error.
+ */
+int64_t emc2o_build_kmap(int32_t kind, const int32_t* in_coords, int64_t n_in, const int32_t grid_in[3],
+                         int32_t n_batch, int64_t capacity_out, int32_t* out_coords, int32_t* nbr,
+                         int32_t grid_out[3]) {
+  if (kind != 0 && kind != 1) return EMC2O_ERR_ARG;
+  if (n_in < 0 || n_batch < 1) return EMC2O_ERR_ARG;
+  const int s = kind == 0 ? 1 : 2;
+  for (int a = 0; a < 3; ++a) grid_out[a] = kind == 0 ? grid_in[a] : (grid_in[a] - 1) / 2 + 1;
+
+  uint64_t* in_keys = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(n_in > 0 ? n_in : 1));
+  if (!in_keys) return EMC2O_ERR_NOMEM;
+  for (int64_t i = 0; i < n_in; ++i) {
+    const int32_t* c = in_coords + 4 * i;
+    if (c[0] < 0 || c[0] >= n_batch || c[1] < 0 || c[1] >= grid_in[2] || c[2] < 0 ||
+        c[2] >= grid_in[1] || c[3] < 0 || c[3] >= grid_in[0]) {
+      free(in_keys);
+      return EMC2O_ERR_ARG;
+    }
+    in_keys[i] = key_of(c[0], c[1], c[2], c[3], grid_in);
+    if (i > 0 && in_keys[i] <= in_keys[i - 1]) { /* must be strictly ascending */
+      free(in_keys);
+      return EMC2O_ERR_ARG;
+    }
+  }
+
+  int64_t n_out = 0;
+  const int32_t* oc = NULL;
+  int32_t* tmp_out = NULL;
+  if (kind == 0) {
+    n_out = n_in;
+    if (n_out > capacity_out) { free(in_keys); return EMC2O_ERR_CAPACITY; }
+    if (out_coords && out_coords != in_coords) memcpy(out_coords, in_coords, sizeof(int32_t) * 4 * (size_t)n_in);
+    oc = in_coords;
+  } else {
+    /* every (input, tap) whose o = (i + 1 - k)/2 is integral and inside grid_out is a candidate */
+    uint64_t* cand = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(n_in > 0 ? 27 * n_in : 1));
+    if (!cand) { free(in_keys); return EMC2O_ERR_NOMEM; }
+    int64_t nc = 0;
+    for (int64_t i = 0; i < n_in; ++i) {
+      const int32_t* c = in_coords + 4 * i;
+      for (int kz = 0; kz < 3; ++kz)
+        for (int ky = 0; ky < 3; ++ky)
+          for (int kx = 0; kx < 3; ++kx) {
+            int tx = c[3] + 1 - kx, ty = c[2] + 1 - ky, tz = c[1] + 1 - kz;
+            if (tx < 0 || ty < 0 || tz < 0) continue;
+            if ((tx & 1) || (ty & 1) || (tz & 1)) continue;
+            int ox = tx / 2, oy = ty / 2, oz = tz / 2;
+            if (ox >= grid_out[0] || oy >= grid_out[1] || oz >= grid_out[2]) continue;
+            cand[nc++] = key_of(c[0], oz, oy, ox, grid_out);
+          }
+    }
+    qsort(cand, (size_t)nc, sizeof(uint64_t), cmp_u64);
+    int64_t u = 0;
+    for (int64_t i = 0; i < nc; ++i)
+      if (i == 0 || cand[i] != cand[i - 1]) cand[u++] = cand[i];
+    n_out = u;
+    if (n_out > capacity_out) { free(cand); free(in_keys); return EMC2O_ERR_CAPACITY; }
+    tmp_out = out_coords;
+    const uint64_t gx = (uint64_t)grid_out[0], gy = (uint64_t)grid_out[1], gz = (uint64_t)grid_out[2];
+    for (int64_t o = 0; o < n_out; ++o) {
+      uint64_t k = cand[o];
+      tmp_out[4 * o + 3] = (int32_t)(k % gx); k /= gx;
+      tmp_out[4 * o + 2] = (int32_t)(k % gy); k /= gy;
+      tmp_out[4 * o + 1] = (int32_t)(k % gz); k /= gz;
+      tmp_out[4 * o + 0] = (int32_t)k;
+    }
+    free(cand);
+    oc = tmp_out;
+  }
+
+  for (int kz = 0; kz < 3; ++kz)
+    for (int ky = 0; ky < 3; ++ky)
+      for (int kx = 0; kx < 3; ++kx) {
+        const int k = (kz * 3 + ky) * 3 + kx;
+        for (int64_t o = 0; o < n_out; ++o) {
+          const int32_t* c = oc + 4 * o;
+          int64_t ix = (int64_t)c[3] * s - 1 + kx;
+          int64_t iy = (int64_t)c[2] * s - 1 + ky;
+          int64_t iz = (int64_t)c[1] * s - 1 + kz;
+          int64_t j = -1;
+          if (ix >= 0 && ix < grid_in[0] && iy >= 0 && iy < grid_in[1] && iz >= 0 && iz < grid_in[2])
+            j = find_key(in_keys, n_in, key_of(c[0], iz, iy, ix, grid_in));
+          nbr[(int64_t)k * capacity_out + o] = (int32_t)j;
+        }
+      }
+  free(in_keys);
+  return n_out;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* sparse convolution                                                                          */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * acc[o][c'] = sum over taps k with nbr[k][o] >= 0, sum over c: x[nbr[k][o]][c] * W[k][c][c'];
+ * y = epi(acc): 0 identity, 1 acc*scale+shift, 2 max(0, acc*scale+shift).  All in fp64, one
+ * rounding to fp32 at the end.  x and w are fp32 (16-bit data is passed already rounded and
+ * up-cast, which is exact).  Returns the number of multiply-accumulates done (= pairs*Cin*Cout),
+ * or a negative error.
+ */
+int64_t emc2o_spconv(const float* x, int64_t n_in, const float* w, const float* scale,
+                     const float* shift, int32_t epilogue, const int32_t* nbr, int64_t nbr_stride,
+                     int64_t n_out, int32_t cin, int32_t cout, float* y) {
+  if (n_out < 0 || n_out > nbr_stride || cin < 1 || cout < 1 || epilogue < 0 || epilogue > 2)
+    return EMC2O_ERR_ARG;
+  if (epilogue != 0 && (!scale || !shift)) return EMC2O_ERR_ARG;
+  double* acc = (double*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)cout, sizeof(double));
+  if (!acc) return EMC2O_ERR_NOMEM;
+  int64_t macs = 0;
+  int bad = 0;
+  for (int k = 0; k < 27; ++k) {
+    const float* wk = w + (int64_t)k * cin * cout;
+    const int32_t* nk = nbr + (int64_t)k * nbr_stride;
+    int64_t pairs = 0;
+#pragma omp parallel for num_threads(g_threads) schedule(static) reduction(+ : pairs) reduction(| : bad)
+    for (int64_t o = 0; o < n_out; ++o) {
+      int64_t j = nk[o];
+      if (j < 0) continue;
+      if (j >= n_in) { bad |= 1; continue; }
+      ++pairs;
+      const float* xr = x + j * cin;
+      double* ar = acc + o * cout;
+      for (int c = 0; c < cin; ++c) {
+        const double xv = (double)xr[c];
+        const float* wr = wk + (int64_t)c * cout;
+        for (int d = 0; d < cout; ++d) ar[d] += xv * (double)wr[d];
+      }
+    }
+    macs += pairs * cin * cout;
+  }
+  if (bad) { free(acc); return EMC2O_ERR_ARG; }
+  for (int64_t o = 0; o < n_out; ++o)
+    for (int d = 0; d < cout; ++d) {
+      double v = acc[o * cout + d];
+      if (epilogue != 0) v = v * (double)scale[d] + (double)shift[d];
+      if (epilogue == 2 && !(v > 0.0)) v = 0.0;
+      y[o * cout + d] = (float)v;
+    }
+  free(acc);
+  return macs;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* projection + bilinear gather                                                                */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * (U, V, w) = P (x, y, z, 1); u = U/w, v = V/w; valid iff w > 0, 0 <= u <= W-1, 0 <= v <= H-1.
+ * Pixel (row j, col i) sits at (u, v) = (i, j).  Bilinear blend of the four surrounding pixels
+ * (upper neighbours clamped to the last row/col); invalid points get an all-zero row.
+ * img: [H][W][C] fp32 (fp16 data up-cast exactly).  out: [n][C] fp32, valid: [n] u8,
+ * uv: [n][2] fp64 or NULL (written for every point with w != 0, NaN otherwise).
+ */
+int32_t emc2o_project_gather(const float* points, int32_t stride_f, int64_t n, const float pm[12],
+                             const float* img, int32_t h, int32_t wd, int32_t c, float* out,
+                             uint8_t* valid, double* uv) {
+  if (n < 0 || stride_f < 3 || h < 1 || wd < 1 || c < 1) return EMC2O_ERR_ARG;
+  for (int64_t i = 0; i < n; ++i) {
+    const float* p = points + i * stride_f;
+    const double x = p[0], y = p[1], z = p[2];
+    const double uu = (double)pm[0] * x + (double)pm[1] * y + (double)pm[2] * z + (double)pm[3];
+    const double vv = (double)pm[4] * x + (double)pm[5] * y + (double)pm[6] * z + (double)pm[7];
+    const double ww = (double)pm[8] * x + (double)pm[9] * y + (double)pm[10] * z + (double)pm[11];
+    float* o = out + i * c;
+    int ok = 0;
+    double u = NAN, v = NAN;
+    if (ww > 0.0) {
+      u = uu / ww;
+      v = vv / ww;
+      ok = (u >= 0.0 && u <= (double)(wd - 1) && v >= 0.0 && v <= (double)(h - 1));
+    } else if (ww < 0.0) {
+      u = uu / ww;
+      v = vv / ww;
+    }
+    if (uv) { uv[2 * i] = u; uv[2 * i + 1] = v; }
+    valid[i] = (uint8_t)ok;
+    if (!ok) {
+      for (int ch = 0; ch < c; ++ch) o[ch] = 0.0f;
+      continue;
+    }
+    int i0 = (int)floor(u), j0 = (int)floor(v);
+    int i1 = i0 + 1 < wd ? i0 + 1 : wd - 1;
+    int j1 = j0 + 1 < h ? j0 + 1 : h - 1;
+    double a = u - (double)i0, b = v - (double)j0;
+    const float* p00 = img + ((int64_t)j0 * wd + i0) * c;
+    const float* p01 = img + ((int64_t)j0 * wd + i1) * c;
+    const float* p10 = img + ((int64_t)j1 * wd + i0) * c;
+    const float* p11 = img + ((int64_t)j1 * wd + i1) * c;
+    for (int ch = 0; ch < c; ++ch) {
+      double g = (1.0 - a) * (1.0 - b) * (double)p00[ch] + a * (1.0 - b) * (double)p01[ch] +
+                 (1.0 - a) * b * (double)p10[ch] + a * b * (double)p11[ch];
+      o[ch] = (float)g;
+    }
+  }
+  return 0;
+}
