@@ -1,0 +1,168 @@
+/*
+ * emc2.h -- C-ABI of the MI355X (gfx950) hot path of the EMC2 LiDAR branch:
+ *   multi-scale voxelization  ->  27-offset kernel map  ->  sparse 3D conv (+ fused affine/ReLU)
+ *   ->  point-to-image projection with bilinear feature gather.
+ *
+ * Conventions
+ *   - Pointers named d_* are DEVICE pointers (HBM, on the context's device); h_* and plain
+ *     struct/array arguments are HOST pointers.  The caller owns every input and output buffer;
+ *     the context owns all scratch (voxel hash, cell-index slots, scan partials, status word),
+ *     allocated once in emc2_create.  No call below allocates or frees device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
+ *     arguments synchronously, enqueue kernels on `stream` and return; they never block unless a
+ *     host count pointer (h_n_*) is given.  Counts (n_voxels, n_out) are produced in DEVICE memory
+ *     so that downstream calls need no host round trip: launches are sized by `capacity`, kernels
+ *     bound themselves by the device count.
+ *   - Errors found on the host are returned at once.  Errors only the device can see (more voxels
+ *     than `capacity`, hash table full) set a device status word; emc2_status_sync returns and
+ *     clears it.  After such an error the outputs of that call are truncated but in bounds.
+ *   - Calls on one context must be issued on one stream at a time (they share its scratch).
+ *   - Voxel order everywhere: ascending key ((b*Gz + z)*Gy + y)*Gx + x, i.e. lexicographic
+ *     (b, z, y, x).  Coordinates are int32 quadruples (b, z, y, x).
+ */
+#ifndef EMC2_H_
+#define EMC2_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  EMC2_OK = 0,
+  EMC2_ERR_INVALID_ARG = 1, /* null/mis-sized argument, size beyond what the context was made for */
+  EMC2_ERR_CAPACITY = 2,    /* more voxels than `capacity`, or the voxel hash filled up            */
+  EMC2_ERR_UNSUPPORTED = 3, /* channel count / dtype / key width the kernels do not cover          */
+  EMC2_ERR_DEVICE = 4       /* a HIP runtime call failed; see emc2_last_error                      */
+} emc2_status;
+
+typedef struct emc2_ctx emc2_ctx;
+
+/*
+ * Create a context on `device`.
+ *   max_points : largest n_points any emc2_voxelize call will pass.
+ *   max_voxels : largest voxel count (capacity) of any level.
+ *   max_cells  : largest n_batch*Gx*Gy*Gz of any grid that is voxelized or mapped.
+ *   n_slots    : number of cell-index slots kept alive at once (>= 1; see emc2_voxelize).
+ * Scratch is about 48 B/point-slot + 8 B per 32 cells per index slot.
+ */
+emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_points, int64_t max_voxels,
+                        int64_t max_cells, int32_t n_slots);
+void emc2_destroy(emc2_ctx* ctx);
+
+/* Synchronise `stream`, return the device status accumulated since the last call (EMC2_OK if none),
+ * and clear it. */
+emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream);
+
+/* Text of the last host-side error on this context (never NULL). */
+const char* emc2_last_error(const emc2_ctx* ctx);
+
+/* Voxel grid: the "pool size" is a runtime parameter (paper Sec. 3.5, Multiscale Pooling is
+ * user-configurable); the grid extent is given, never derived from bounds. */
+typedef struct {
+  float lo[3];      /* lower bound x, y, z                                             */
+  float vs[3];      /* voxel size  x, y, z  (> 0)                                      */
+  int32_t grid[3];  /* Gx, Gy, Gz                                                      */
+  int32_t n_batch;  /* number of frames B >= 1                                         */
+  float r2_min;     /* keep a point iff r2_min <= fl(fl(x*x)+fl(y*y)) < r2_max         */
+  float r2_max;     /*   (0, +inf) switches the range filter off                       */
+  int32_t stride_f; /* floats per point row (>= 4): x, y, z, intensity, ...            */
+} emc2_voxel_spec;
+
+typedef enum { EMC2_F32 = 0, EMC2_F16 = 1, EMC2_BF16 = 2 } emc2_dtype;
+
+/*
+ * Voxelization with mean voxel features (paper Sec. 2: LiDAR methods process point clouds via
+ * voxelization; Sec. 3.1: the data bridge prepares voxel features for the experts; Sec. 3.5:
+ * configurable pool size -> call once per scale for multi-scale output).
+ *
+ * A point is kept iff, per axis a, t = fl(fl(p_a - lo_a) / vs_a) (IEEE fp32, true division)
+ * satisfies 0 <= t < G_a, its batch id is in [0, n_batch), its intensity is finite and it passes
+ * the range filter.  Its cell is floor(t).  Outputs, in ascending key order:
+ *   d_coords [capacity][4] int32 (b, z, y, x)
+ *   d_feats  [capacity][4] fp32  mean (x, y, z, intensity) over ALL points of the voxel
+ *   d_counts [capacity]    int32 points per voxel
+ *   d_feats_lp [capacity][4] copy of d_feats rounded (RNE) to `lp_dtype` (F16/BF16); NULL to skip
+ *   d_n_voxels  device int32 (always written); h_n_voxels host int32, NULL = no sync
+ * d_batch: [n_points] int32 or NULL (all points in frame 0).
+ * index_slot in [0, n_slots): the cell index of the produced voxel set is left in that slot for
+ * emc2_build_kmap to reuse; it stays valid until another call writes the same slot.
+ * Means are accumulated with fp32 atomics (order not fixed; result within a few ulp of exact).
+ */
+emc2_status emc2_voxelize(emc2_ctx* ctx, const float* d_points, const int32_t* d_batch,
+                          int64_t n_points, const emc2_voxel_spec* spec, int64_t capacity,
+                          int32_t* d_coords, float* d_feats, int32_t* d_counts, void* d_feats_lp,
+                          emc2_dtype lp_dtype, int32_t* d_n_voxels, int32_t* h_n_voxels,
+                          int32_t index_slot, void* stream);
+
+typedef enum { EMC2_CONV_SUBM = 0, EMC2_CONV_STRIDED = 1 } emc2_conv_kind;
+
+/*
+ * Kernel map (rulebook) of a 3x3x3 sparse convolution over the non-empty voxels (paper Sec. 3.5:
+ * only non-empty voxels are computed, O(N*C_v); Sec. 3.6: prefix-sum index search).
+ *
+ * Tap k = (kz*3 + ky)*3 + kx, kx,ky,kz in {0,1,2}.  Output site o reads input site
+ * i = o*s - 1 + (kx, ky, kz) in the same frame (cross-correlation), with
+ *   SUBM    : s = 1, outputs == inputs (same order), grid_out = grid_in;
+ *   STRIDED : s = 2 (k3 s2 p1), grid_out = (G-1)/2 + 1 per axis; output o is active iff at least
+ *             one of its 27 taps reads an active input; outputs in ascending key order.
+ * d_nbr[k*capacity_out + o] = index of the input voxel read by (o, k), or -1.
+ *
+ *   d_in_coords [n_in][4] ascending key; d_n_in device int32 count.
+ *   in_slot  : index slot holding the cell index of exactly these inputs (left there by
+ *              emc2_voxelize or by a STRIDED call's out_slot), or -1 to rebuild it from d_in_coords.
+ *   out_slot : STRIDED only: slot that receives the cell index of the outputs (or -1: internal,
+ *              not kept).  Must differ from in_slot.
+ *   d_out_coords [capacity_out][4]: STRIDED: written.  SUBM: may be NULL or == d_in_coords;
+ *              otherwise receives a copy.
+ *   d_n_out  device int32 (written; SUBM: copy of *d_n_in); h_n_out host, NULL = no sync.
+ *   grid_out host int32[3], written.
+ * capacity_out must be >= the true output count (else EMC2_ERR_CAPACITY via the status word; the
+ * map is then truncated to the first capacity_out outputs).
+ */
+emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_in_coords,
+                            const int32_t* d_n_in, int64_t capacity_in, const int32_t grid_in[3],
+                            int32_t n_batch, int32_t in_slot, int32_t out_slot, int64_t capacity_out,
+                            int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr,
+                            int32_t grid_out[3], int32_t* h_n_out, void* stream);
+
+typedef enum { EMC2_EPI_NONE = 0, EMC2_EPI_AFFINE = 1, EMC2_EPI_AFFINE_RELU = 2 } emc2_epilogue;
+
+/*
+ * Sparse convolution over a kernel map, output-stationary gather-GEMM (paper Sec. 3.5: customised
+ * 3D sparse convolution, the bulk of inference time; Sec. 3.6: graph fusion -> the folded-BN affine
+ * and ReLU are fused into the epilogue):
+ *   acc[o][c'] = sum_{k : nbr[k][o] >= 0} sum_c in[nbr[k][o]][c] * w[k][c][c']      (fp32 accumulate)
+ *   out[o][c'] = acc | acc*scale[c'] + shift[c'] | max(0, acc*scale[c'] + shift[c'])
+ *   d_in  [n_in][Cin], d_w [27][Cin][Cout], d_out [capacity_out][Cout]: all of `dtype`
+ *   d_scale, d_shift [Cout] fp32 (NULL iff EMC2_EPI_NONE)
+ *   d_nbr [27][capacity_out] from emc2_build_kmap; d_n_out device int32 count of outputs.
+ * F16/BF16 run on MFMA for Cin, Cout in {16, 32, 64, 128} (Cin = 4 also accepted); other channel
+ * counts and F32 run on the vector ALU.  Rows [n_out, capacity_out) of d_out are not written.
+ */
+emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
+                        const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
+                        const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out,
+                        int32_t cin, int32_t cout, void* d_out, void* stream);
+
+/*
+ * Point -> image projection with bilinear feature gather (paper Sec. 3.1: image features are
+ * aligned with 3D positions for fusion; Fig. 5 caption: sites without a match get zero-filled
+ * features).
+ *   (U, V, w) = P (x, y, z, 1) in fp64, u = U/w, v = V/w; valid iff w > 0, 0 <= u <= W-1,
+ *   0 <= v <= H-1.  Pixel (row j, col i) sits at (u, v) = (i, j).  The four neighbours
+ *   (floor and floor+1, clamped to the last row/col) are blended in fp32 and rounded once to fp16.
+ *   Invalid points get an all-zero row and valid = 0.
+ *   d_points [n][stride_f] fp32; P host float[12] row-major 3x4; d_img [H][W][C] fp16, C even and
+ *   <= 1024; d_out [n][C] fp16; d_valid [n] uint8; d_uv [n][2] fp32 or NULL.
+ */
+emc2_status emc2_project_gather(emc2_ctx* ctx, const float* d_points, int32_t stride_f,
+                                int64_t n_points, const float P[12], const void* d_img, int32_t H,
+                                int32_t W, int32_t C, void* d_out, uint8_t* d_valid, float* d_uv,
+                                void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EMC2_H_ */

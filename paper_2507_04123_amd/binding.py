@@ -1,0 +1,212 @@
+"""ctypes binding over libemc2.so: argument marshalling only, every step runs in the HIP kernels.
+
+Tensors are torch CUDA(=HIP) tensors used purely as device buffers; the current torch stream is
+passed as the HIP stream.  There is no CPU fallback: if the library is missing or no GPU is present
+the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+from .configs import VoxelSpec
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libemc2.so")
+
+OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = 0, 1, 2, 3, 4
+F32, F16, BF16 = 0, 1, 2
+SUBM, STRIDED = 0, 1
+EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
+
+_TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
+
+EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
+           "emc2_build_kmap", "emc2_spconv", "emc2_project_gather"]
+
+
+class Emc2Error(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"emc2 status {status}: {msg}")
+        self.status = status
+
+
+class _VoxelSpecC(ctypes.Structure):
+    _fields_ = [("lo", ctypes.c_float * 3), ("vs", ctypes.c_float * 3), ("grid", ctypes.c_int32 * 3),
+                ("n_batch", ctypes.c_int32), ("r2_min", ctypes.c_float), ("r2_max", ctypes.c_float),
+                ("stride_f", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libemc2.so (build it first with ``python -m paper_2507_04123_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build() or paper_2507_04123_amd/build.py")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    lib.emc2_create.restype = ctypes.c_int
+    lib.emc2_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64, i32]
+    lib.emc2_destroy.restype = None
+    lib.emc2_destroy.argtypes = [vp]
+    lib.emc2_status_sync.restype = ctypes.c_int
+    lib.emc2_status_sync.argtypes = [vp, vp]
+    lib.emc2_last_error.restype = ctypes.c_char_p
+    lib.emc2_last_error.argtypes = [vp]
+    lib.emc2_voxelize.restype = ctypes.c_int
+    lib.emc2_voxelize.argtypes = [vp, vp, vp, i64, ctypes.POINTER(_VoxelSpecC), i64, vp, vp, vp, vp, ctypes.c_int, vp,
+                                  ctypes.POINTER(i32), i32, vp]
+    lib.emc2_build_kmap.restype = ctypes.c_int
+    lib.emc2_build_kmap.argtypes = [vp, ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i32, i32, i64, vp, vp, vp,
+                                    ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+    lib.emc2_spconv.restype = ctypes.c_int
+    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int, vp, vp, i64, i32, i32, vp, vp]
+    lib.emc2_project_gather.restype = ctypes.c_int
+    lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_check(t: torch.Tensor, dtype: torch.dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name}: need a contiguous {dtype} device tensor, got {t.dtype} on {t.device}")
+
+
+class Context:
+    """Owns the library's scratch on one GPU (see emc2_create)."""
+
+    def __init__(self, max_points: int, max_voxels: int, max_cells: int, n_slots: int = 4, device: int = 0):
+        if not torch.cuda.is_available():
+            raise RuntimeError("emc2 needs a GPU: there is no CPU path")
+        self.lib = load_library()
+        self.device = device
+        h = ctypes.c_void_p()
+        st = self.lib.emc2_create(ctypes.byref(h), device, max_points, max_voxels, max_cells, n_slots)
+        if st != OK:
+            raise Emc2Error(st, "emc2_create failed")
+        self.h = h
+        self.max_voxels = max_voxels
+
+    def close(self) -> None:
+        if getattr(self, "h", None):
+            self.lib.emc2_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _chk(self, st: int) -> None:
+        if st != OK:
+            raise Emc2Error(st, self.lib.emc2_last_error(self.h).decode())
+
+    def status_sync(self) -> None:
+        self._chk(self.lib.emc2_status_sync(self.h, _stream()))
+
+    # ------------------------------------------------------------------------------------------
+    def voxelize(self, points: torch.Tensor, batch: Optional[torch.Tensor], spec: VoxelSpec, capacity: int,
+                 coords: torch.Tensor, feats: torch.Tensor, counts: torch.Tensor, n_voxels: torch.Tensor,
+                 feats_lp: Optional[torch.Tensor] = None, index_slot: int = 0, sync_count: bool = False) -> Optional[int]:
+        _dev_check(points, torch.float32, "points")
+        _dev_check(coords, torch.int32, "coords")
+        _dev_check(feats, torch.float32, "feats")
+        _dev_check(counts, torch.int32, "counts")
+        _dev_check(n_voxels, torch.int32, "n_voxels")
+        n, stride = (points.shape[0], points.shape[1]) if points.dim() == 2 else (0, 4)
+        if coords.numel() < 4 * capacity or feats.numel() < 4 * capacity or counts.numel() < capacity:
+            raise ValueError("output buffers smaller than capacity")
+        if batch is not None:
+            _dev_check(batch, torch.int32, "batch")
+            if batch.numel() != n:
+                raise ValueError("batch length != number of points")
+        lp_dtype = F16
+        if feats_lp is not None:
+            lp_dtype = {torch.float16: F16, torch.bfloat16: BF16}[feats_lp.dtype]
+            if feats_lp.numel() < 4 * capacity or not feats_lp.is_cuda:
+                raise ValueError("feats_lp smaller than capacity")
+        cs = _VoxelSpecC((ctypes.c_float * 3)(*spec.lo), (ctypes.c_float * 3)(*spec.vs), (ctypes.c_int32 * 3)(*spec.grid),
+                         spec.n_batch, spec.r2_min, spec.r2_max, stride)
+        h_n = ctypes.c_int32(0)
+        self._chk(self.lib.emc2_voxelize(self.h, _ptr(points), _ptr(batch), n, ctypes.byref(cs), capacity, _ptr(coords),
+                                         _ptr(feats), _ptr(counts), _ptr(feats_lp), lp_dtype, _ptr(n_voxels),
+                                         ctypes.byref(h_n) if sync_count else None, index_slot, _stream()))
+        return int(h_n.value) if sync_count else None
+
+    def build_kmap(self, kind: int, in_coords: torch.Tensor, n_in: torch.Tensor, capacity_in: int, grid_in: Sequence[int],
+                   n_batch: int, capacity_out: int, nbr: torch.Tensor, n_out: torch.Tensor,
+                   out_coords: Optional[torch.Tensor] = None, in_slot: int = -1, out_slot: int = -1,
+                   sync_count: bool = False) -> Tuple[Tuple[int, int, int], Optional[int]]:
+        _dev_check(in_coords, torch.int32, "in_coords")
+        _dev_check(n_in, torch.int32, "n_in")
+        _dev_check(nbr, torch.int32, "nbr")
+        _dev_check(n_out, torch.int32, "n_out")
+        if in_coords.numel() < 4 * capacity_in or nbr.numel() < 27 * capacity_out:
+            raise ValueError("buffers smaller than capacity")
+        if out_coords is not None:
+            _dev_check(out_coords, torch.int32, "out_coords")
+            if out_coords.numel() < 4 * capacity_out:
+                raise ValueError("out_coords smaller than capacity_out")
+        g_in = (ctypes.c_int32 * 3)(*grid_in)
+        g_out = (ctypes.c_int32 * 3)()
+        h_n = ctypes.c_int32(0)
+        self._chk(self.lib.emc2_build_kmap(self.h, kind, _ptr(in_coords), _ptr(n_in), capacity_in, g_in, n_batch, in_slot,
+                                           out_slot, capacity_out, _ptr(out_coords), _ptr(n_out), _ptr(nbr), g_out,
+                                           ctypes.byref(h_n) if sync_count else None, _stream()))
+        return (g_out[0], g_out[1], g_out[2]), (int(h_n.value) if sync_count else None)
+
+    def spconv(self, dtype: int, x: torch.Tensor, w: torch.Tensor, scale: Optional[torch.Tensor],
+               shift: Optional[torch.Tensor], epilogue: int, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int,
+               out: torch.Tensor) -> None:
+        td = _TORCH_DTYPE[dtype]
+        _dev_check(x, td, "x")
+        _dev_check(w, td, "w")
+        _dev_check(out, td, "out")
+        _dev_check(nbr, torch.int32, "nbr")
+        _dev_check(n_out, torch.int32, "n_out")
+        if w.dim() != 3 or w.shape[0] != 27 or x.dim() != 2 or x.shape[1] != w.shape[1]:
+            raise ValueError("w must be [27][Cin][Cout] and x [n][Cin]")
+        cin, cout = int(w.shape[1]), int(w.shape[2])
+        if out.numel() < capacity_out * cout or nbr.numel() < 27 * capacity_out:
+            raise ValueError("out / nbr smaller than capacity_out")
+        if scale is not None:
+            _dev_check(scale, torch.float32, "scale")
+            _dev_check(shift, torch.float32, "shift")
+            if scale.numel() != cout or shift.numel() != cout:
+                raise ValueError("scale/shift must have Cout entries")
+        self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
+                                       _ptr(n_out), capacity_out, cin, cout, _ptr(out), _stream()))
+
+    def project_gather(self, points: torch.Tensor, pmat: Sequence[float], img: torch.Tensor, out: torch.Tensor,
+                       valid: torch.Tensor, uv: Optional[torch.Tensor] = None) -> None:
+        _dev_check(points, torch.float32, "points")
+        _dev_check(img, torch.float16, "img")
+        _dev_check(out, torch.float16, "out")
+        _dev_check(valid, torch.uint8, "valid")
+        n, stride = points.shape
+        h, w, c = img.shape
+        if out.numel() < n * c or valid.numel() < n:
+            raise ValueError("out / valid too small")
+        if uv is not None:
+            _dev_check(uv, torch.float32, "uv")
+            if uv.numel() < 2 * n:
+                raise ValueError("uv too small")
+        pm = (ctypes.c_float * 12)(*[float(v) for v in pmat])
+        self._chk(self.lib.emc2_project_gather(self.h, _ptr(points), stride, n, pm, _ptr(img), h, w, c, _ptr(out),
+                                               _ptr(valid), _ptr(uv), _stream()))

@@ -1,0 +1,140 @@
+// Cell index (occupancy bits + prefix-summed ranks): clear, mark, scan.
+// The scan is the prefix-sum index search of the paper's Sec. 3.6: after it, the voxel index of
+// any active cell is found with one 8-byte load.
+#include "common.h"
+
+namespace {
+
+__global__ void __launch_bounds__(256) k_index_clear(uint4* __restrict__ p, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+    p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+__global__ void __launch_bounds__(256) k_index_mark_coords(cellword_t* __restrict__ idx,
+                                                           const int4* __restrict__ coords,
+                                                           const int32_t* __restrict__ d_n, int64_t capacity,
+                                                           int gx, int gy, int gz, int n_batch) {
+  int64_t n = *d_n;
+  if (n > capacity) n = capacity;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int4 c = coords[i];  // (b, z, y, x)
+  if ((unsigned)c.x >= (unsigned)n_batch || (unsigned)c.y >= (unsigned)gz || (unsigned)c.z >= (unsigned)gy ||
+      (unsigned)c.w >= (unsigned)gx)
+    return;  // malformed coordinate: ignore rather than write out of bounds
+  const uint64_t key = (((uint64_t)c.x * gz + (uint64_t)c.y) * gy + (uint64_t)c.z) * gx + (uint64_t)c.w;
+  atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+}
+
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint32_t t = __shfl_up(v, d, 64);
+    if ((int)(threadIdx.x & 63) >= d) v += t;
+  }
+  return v;
+}
+
+// Per-block popcount totals.  Thread t owns the 8 consecutive words [8t, 8t+8) of its tile.
+__global__ void __launch_bounds__(256) k_scan_reduce(const cellword_t* __restrict__ idx, int64_t n_words,
+                                                     uint32_t* __restrict__ partials) {
+  const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (base + j < n_words) s += __popc(idx[base + j].x);
+  __shared__ uint32_t wsum[4];
+  const uint32_t inc = wave_inclusive_scan(s);
+  if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+  __syncthreads();
+  if (threadIdx.x == 0) partials[blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+}
+
+// Single block: exclusive scan of the block totals in place, total to *d_total (clamped).
+__global__ void __launch_bounds__(1024) k_scan_partials(uint32_t* __restrict__ partials, int64_t n, int64_t capacity,
+                                                        int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags) {
+  __shared__ uint32_t wsum[16];
+  __shared__ uint32_t carry_s;
+  if (threadIdx.x == 0) carry_s = 0;
+  __syncthreads();
+  for (int64_t start = 0; start < n; start += 1024) {
+    const int64_t i = start + threadIdx.x;
+    const uint32_t v = i < n ? partials[i] : 0u;
+    const uint32_t inc = wave_inclusive_scan(v);
+    if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+    __syncthreads();
+    uint32_t wbase = 0;
+    const int w = threadIdx.x >> 6;
+    for (int j = 0; j < w; ++j) wbase += wsum[j];
+    const uint32_t carry = carry_s;
+    if (i < n) partials[i] = carry + wbase + inc - v;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry_s = carry + wbase + inc;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t total = carry_s;
+    if ((int64_t)total > capacity) {
+      atomicOr(d_flags, EMC2_DEVFLAG_CAPACITY);
+      *d_total = (int32_t)capacity;
+    } else {
+      *d_total = (int32_t)total;
+    }
+  }
+}
+
+// Write each word's exclusive prefix (.y).
+__global__ void __launch_bounds__(256) k_scan_apply(cellword_t* __restrict__ idx, int64_t n_words,
+                                                    const uint32_t* __restrict__ partials) {
+  const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
+  uint32_t bits[8];
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    bits[j] = (base + j < n_words) ? idx[base + j].x : 0u;
+    s += __popc(bits[j]);
+  }
+  __shared__ uint32_t wsum[4];
+  const uint32_t inc = wave_inclusive_scan(s);
+  if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+  __syncthreads();
+  uint32_t run = partials[blockIdx.x] + inc - s;
+  const int w = threadIdx.x >> 6;
+  for (int j = 0; j < w; ++j) run += wsum[j];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
+    run += __popc(bits[j]);
+  }
+}
+
+}  // namespace
+
+void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, hipStream_t stream) {
+  (void)ctx;
+  const int64_t n_words = emc2_div_up(n_cells, 32);
+  const int64_t n16 = emc2_div_up(n_words, 2);  // slot has one spare word, so rounding up is in bounds
+  int64_t blocks = emc2_div_up(n16, 256 * 4);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 65536) blocks = 65536;
+  hipLaunchKernelGGL(k_index_clear, dim3((unsigned)blocks), dim3(256), 0, stream, (uint4*)idx, n16);
+}
+
+void emc2_index_mark_coords(emc2_ctx* ctx, cellword_t* idx, const int32_t* d_coords, const int32_t* d_n,
+                            int64_t capacity, const int32_t grid[3], int32_t n_batch, hipStream_t stream) {
+  (void)ctx;
+  if (capacity < 1) return;
+  hipLaunchKernelGGL(k_index_mark_coords, dim3((unsigned)emc2_div_up(capacity, 256)), dim3(256), 0, stream, idx,
+                     (const int4*)d_coords, d_n, capacity, grid[0], grid[1], grid[2], n_batch);
+}
+
+void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t capacity, int32_t* d_total,
+                     hipStream_t stream) {
+  const int64_t n_words = emc2_div_up(n_cells, 32);
+  const int64_t n_blocks = emc2_div_up(n_words, EMC2_SCAN_TILE);
+  hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);
+  hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, stream, ctx->partials, n_blocks, capacity, d_total,
+                     ctx->dev_words);
+  hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);
+}

@@ -1,0 +1,82 @@
+// Internal declarations shared by the translation units of libemc2.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "emc2.h"
+
+// ---------------------------------------------------------------------------------------------
+// Cell index: one 8-byte word per 32 consecutive cells of the linear key space
+//   .x = occupancy bits (bit j <=> cell 32*w + j is an active voxel)
+//   .y = number of active cells in all earlier words (exclusive prefix sum of popcounts)
+// Because voxels are listed in ascending key order, the voxel index of an active cell is simply
+// its rank: word.y + popcount(word.x & lower-bit mask).  This is the prefix-sum index search of
+// the paper's Sec. 3.6, giving an O(1) lookup.
+// ---------------------------------------------------------------------------------------------
+typedef uint2 cellword_t;
+
+__device__ __forceinline__ int32_t cell_lookup(const cellword_t* __restrict__ idx, uint64_t key) {
+  const cellword_t w = idx[key >> 5];
+  const uint32_t bit = (uint32_t)key & 31u;
+  if (!((w.x >> bit) & 1u)) return -1;
+  return (int32_t)(w.y + __popc(w.x & ((1u << bit) - 1u)));
+}
+
+// Voxel hash record (open addressing, linear probing): the key and its running sums share one
+// 32-byte sector so that a point touches a single sector for the CAS and its five atomic adds.
+struct __attribute__((aligned(32))) VoxRec {
+  unsigned long long key;  // EMPTY_KEY when free
+  float sum[4];            // x, y, z, intensity
+  uint32_t count;
+  uint32_t pad;
+};
+static_assert(sizeof(VoxRec) == 32, "VoxRec must be 32 bytes");
+
+#define EMC2_EMPTY_KEY 0xFFFFFFFFFFFFFFFFull
+
+// Device status bits (OR-ed by kernels, read by emc2_status_sync).
+#define EMC2_DEVFLAG_CAPACITY 1
+#define EMC2_DEVFLAG_HASH_FULL 2
+
+struct SlotMeta {
+  int32_t grid[3];
+  int32_t n_batch;
+  bool valid;
+};
+
+struct emc2_ctx {
+  int device;
+  int64_t max_points, max_voxels, max_cells;
+  int32_t n_slots;          // user-visible slots; two more internal ones follow
+  int64_t slot_words;       // cellwords per slot
+  cellword_t** slots;       // host array [n_slots + 2] of device pointers
+  SlotMeta* meta;           // host array [n_slots + 2]
+  VoxRec* table;            // [table_slots]
+  int64_t table_slots;      // power of two
+  int32_t* uslot;           // [max_voxels] hash slots of the distinct voxels, in claim order
+  uint32_t* partials;       // scan partial sums
+  int64_t n_partials;
+  int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count
+  int32_t* pinned;          // pinned host staging for counts / status (4 ints)
+  char err[256];
+};
+
+#define EMC2_SCAN_TILE 2048  // cellwords per scan block (256 threads x 8)
+
+// host helpers (context.hip)
+emc2_status emc2_fail(emc2_ctx* ctx, emc2_status st, const char* fmt, ...);
+emc2_status emc2_check_hip(emc2_ctx* ctx, hipError_t e, const char* what);
+bool emc2_grid_ok(const int32_t grid[3], int32_t n_batch, int64_t* n_cells);
+
+// cell-index construction (cellindex.hip); all asynchronous on `stream`
+void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, hipStream_t stream);
+// exclusive scan of popcounts over ceil(n_cells/32) words; writes min(total, capacity) to d_total
+// and raises EMC2_DEVFLAG_CAPACITY when total > capacity
+void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t capacity, int32_t* d_total,
+                     hipStream_t stream);
+// set the bits of coords[0..*d_n) (b,z,y,x) in a cleared index
+void emc2_index_mark_coords(emc2_ctx* ctx, cellword_t* idx, const int32_t* d_coords, const int32_t* d_n,
+                            int64_t capacity, const int32_t grid[3], int32_t n_batch, hipStream_t stream);
+
+static inline int64_t emc2_div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -1,0 +1,123 @@
+// Context: owns every scratch buffer of the library; nothing else allocates device memory.
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "common.h"
+
+emc2_status emc2_fail(emc2_ctx* ctx, emc2_status st, const char* fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return st;
+}
+
+emc2_status emc2_check_hip(emc2_ctx* ctx, hipError_t e, const char* what) {
+  if (e == hipSuccess) return EMC2_OK;
+  return emc2_fail(ctx, EMC2_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool emc2_grid_ok(const int32_t grid[3], int32_t n_batch, int64_t* n_cells) {
+  if (!grid || n_batch < 1) return false;
+  for (int a = 0; a < 3; ++a)
+    if (grid[a] < 1 || grid[a] > (1 << 20)) return false;
+  // keep the linear key (and 32*word index arithmetic) comfortably inside 63 bits
+  const long double cells = (long double)grid[0] * grid[1] * grid[2] * n_batch;
+  if (cells > 1.0e15L) return false;
+  *n_cells = (int64_t)grid[0] * grid[1] * grid[2] * n_batch;
+  return true;
+}
+
+static int64_t pow2_at_least(int64_t v) {
+  int64_t p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_points, int64_t max_voxels,
+                                   int64_t max_cells, int32_t n_slots) {
+  if (!out) return EMC2_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (max_points < 1 || max_voxels < 1 || max_cells < 1 || n_slots < 1 || n_slots > 64)
+    return EMC2_ERR_INVALID_ARG;
+  if (max_points > (1ll << 30) || max_voxels > (1ll << 30)) return EMC2_ERR_INVALID_ARG;
+  emc2_ctx* ctx = (emc2_ctx*)calloc(1, sizeof(emc2_ctx));
+  if (!ctx) return EMC2_ERR_DEVICE;
+  ctx->device = device;
+  ctx->max_points = max_points;
+  ctx->max_voxels = max_voxels;
+  ctx->max_cells = max_cells;
+  ctx->n_slots = n_slots;
+  ctx->err[0] = 0;
+  emc2_status st = EMC2_OK;
+#define TRY(call, what)                                   \
+  do {                                                    \
+    st = emc2_check_hip(ctx, (call), what);               \
+    if (st != EMC2_OK) goto fail;                         \
+  } while (0)
+  TRY(hipSetDevice(device), "hipSetDevice");
+  ctx->slot_words = emc2_div_up(max_cells, 32) + 1;
+  ctx->slots = (cellword_t**)calloc((size_t)n_slots + 2, sizeof(cellword_t*));
+  ctx->meta = (SlotMeta*)calloc((size_t)n_slots + 2, sizeof(SlotMeta));
+  if (!ctx->slots || !ctx->meta) { st = EMC2_ERR_DEVICE; goto fail; }
+  for (int s = 0; s < n_slots + 2; ++s)
+    TRY(hipMalloc((void**)&ctx->slots[s], sizeof(cellword_t) * (size_t)ctx->slot_words), "hipMalloc(index slot)");
+  // the hash holds at most one entry per point and at most max_voxels useful ones; twice that many slots
+  ctx->table_slots = pow2_at_least(2 * (max_points < max_voxels ? max_points : max_voxels));
+  if (ctx->table_slots < 1024) ctx->table_slots = 1024;
+  TRY(hipMalloc((void**)&ctx->table, sizeof(VoxRec) * (size_t)ctx->table_slots), "hipMalloc(voxel hash)");
+  TRY(hipMalloc((void**)&ctx->uslot, sizeof(int32_t) * (size_t)max_voxels), "hipMalloc(uslot)");
+  ctx->n_partials = emc2_div_up(ctx->slot_words, EMC2_SCAN_TILE) + 1;
+  TRY(hipMalloc((void**)&ctx->partials, sizeof(uint32_t) * (size_t)ctx->n_partials), "hipMalloc(partials)");
+  TRY(hipMalloc((void**)&ctx->dev_words, sizeof(int32_t) * 8), "hipMalloc(dev_words)");
+  TRY(hipMemset(ctx->dev_words, 0, sizeof(int32_t) * 8), "hipMemset(dev_words)");
+  TRY(hipHostMalloc((void**)&ctx->pinned, sizeof(int32_t) * 8, hipHostMallocDefault), "hipHostMalloc");
+  TRY(hipDeviceSynchronize(), "hipDeviceSynchronize");
+#undef TRY
+  *out = ctx;
+  return EMC2_OK;
+fail:
+  emc2_destroy(ctx);
+  return st;
+}
+
+extern "C" void emc2_destroy(emc2_ctx* ctx) {
+  if (!ctx) return;
+  (void)hipSetDevice(ctx->device);
+  if (ctx->slots) {
+    for (int s = 0; s < ctx->n_slots + 2; ++s)
+      if (ctx->slots[s]) (void)hipFree(ctx->slots[s]);
+    free(ctx->slots);
+  }
+  free(ctx->meta);
+  if (ctx->table) (void)hipFree(ctx->table);
+  if (ctx->uslot) (void)hipFree(ctx->uslot);
+  if (ctx->partials) (void)hipFree(ctx->partials);
+  if (ctx->dev_words) (void)hipFree(ctx->dev_words);
+  if (ctx->pinned) (void)hipHostFree(ctx->pinned);
+  free(ctx);
+}
+
+extern "C" emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  emc2_status st = emc2_check_hip(ctx, hipMemcpyAsync(ctx->pinned, ctx->dev_words, sizeof(int32_t),
+                                                      hipMemcpyDeviceToHost, s), "hipMemcpyAsync(status)");
+  if (st != EMC2_OK) return st;
+  st = emc2_check_hip(ctx, hipMemsetAsync(ctx->dev_words, 0, sizeof(int32_t), s), "hipMemsetAsync(status)");
+  if (st != EMC2_OK) return st;
+  st = emc2_check_hip(ctx, hipStreamSynchronize(s), "hipStreamSynchronize");
+  if (st != EMC2_OK) return st;
+  const int flags = ctx->pinned[0];
+  if (flags & (EMC2_DEVFLAG_CAPACITY | EMC2_DEVFLAG_HASH_FULL))
+    return emc2_fail(ctx, EMC2_ERR_CAPACITY, "device reported %s%s",
+                     (flags & EMC2_DEVFLAG_CAPACITY) ? "[more voxels than capacity]" : "",
+                     (flags & EMC2_DEVFLAG_HASH_FULL) ? "[voxel hash full]" : "");
+  return EMC2_OK;
+}
+
+extern "C" const char* emc2_last_error(const emc2_ctx* ctx) { return ctx ? ctx->err : "null context"; }

@@ -1,0 +1,205 @@
+// Kernel map (rulebook) for the 27 offsets of a 3x3x3 sparse conv (paper Sec. 3.5: only non-empty
+// voxels are computed; Sec. 3.6: prefix-sum index search).
+//
+// SUBM   : for every active voxel o and tap k, look up cell(o) - 1 + k in the input cell index.
+// STRIDED: each input marks the (at most 8) outputs whose 3x3x3 window contains it in the output
+//          cell index; the scan ranks them (= ascending key order); the set bits are expanded to
+//          coordinates; then every output probes the input index at 2*o - 1 + k.
+#include "common.h"
+
+namespace {
+
+__global__ void __launch_bounds__(256) k_strided_mark(const int4* __restrict__ in_coords, const int32_t* __restrict__ d_n_in,
+                                                      int64_t capacity_in, cellword_t* __restrict__ out_idx, int gox,
+                                                      int goy, int goz, int gx, int gy, int gz, int n_batch) {
+  int64_t n = *d_n_in;
+  if (n > capacity_in) n = capacity_in;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int4 c = in_coords[i];  // (b, z, y, x)
+  if ((unsigned)c.x >= (unsigned)n_batch || (unsigned)c.y >= (unsigned)gz || (unsigned)c.z >= (unsigned)gy ||
+      (unsigned)c.w >= (unsigned)gx)
+    return;  // malformed coordinate: ignore rather than write out of bounds
+  // input coordinate v is read by outputs o with 2o-1 <= v <= 2o+1: o = v/2 if v even, (v-1)/2 and (v+1)/2 if odd
+  const int x0 = c.w >> 1, nx = ((c.w & 1) && (x0 + 1 < gox)) ? 2 : 1;
+  const int y0 = c.z >> 1, ny = ((c.z & 1) && (y0 + 1 < goy)) ? 2 : 1;
+  const int z0 = c.y >> 1, nz = ((c.y & 1) && (z0 + 1 < goz)) ? 2 : 1;
+  for (int dz = 0; dz < nz; ++dz)
+    for (int dy = 0; dy < ny; ++dy) {
+      const uint64_t row = (((uint64_t)c.x * goz + (uint64_t)(z0 + dz)) * goy + (uint64_t)(y0 + dy)) * gox;
+      for (int dx = 0; dx < nx; ++dx) {
+        const uint64_t key = row + (uint64_t)(x0 + dx);
+        atomicOr(&out_idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+      }
+    }
+}
+
+// One thread per cellword: expand set bits into coordinates at their rank.
+__global__ void __launch_bounds__(256) k_expand_coords(const cellword_t* __restrict__ idx, int64_t n_words, int64_t capacity,
+                                                       int gx, int gy, int gz, int4* __restrict__ coords) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= n_words) return;
+  const cellword_t cw = idx[w];
+  uint32_t bits = cw.x;
+  int64_t r = cw.y;
+  while (bits) {
+    const int j = __ffs((int)bits) - 1;
+    bits &= bits - 1;
+    if (r < capacity) {
+      uint64_t k = (uint64_t)w * 32 + (uint64_t)j;
+      const int x = (int)(k % (uint64_t)gx); k /= (uint64_t)gx;
+      const int y = (int)(k % (uint64_t)gy); k /= (uint64_t)gy;
+      const int z = (int)(k % (uint64_t)gz); k /= (uint64_t)gz;
+      coords[r] = make_int4((int)k, z, y, x);
+    }
+    ++r;
+  }
+}
+
+// One thread per output voxel: 27 lookups in the input cell index.  S = stride (1 or 2).
+template <int S>
+__global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ out_coords, const int32_t* __restrict__ d_n_out,
+                                               int64_t capacity_out, const cellword_t* __restrict__ in_idx,
+                                               const int32_t* __restrict__ d_n_in, int gx, int gy, int gz, int n_batch,
+                                               int32_t* __restrict__ nbr) {
+  int64_t n = *d_n_out;
+  if (n > capacity_out) n = capacity_out;
+  const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= n) return;
+  const int32_t n_in = *d_n_in;
+  int4 c = out_coords[o];  // (b, z, y, x)
+  // malformed coordinate: emit an empty column (the per-tap range checks below keep every lookup in bounds)
+  const bool sane = (unsigned)c.x < (unsigned)n_batch && (unsigned)c.y <= (1u << 20) && (unsigned)c.z <= (1u << 20) &&
+                    (unsigned)c.w <= (1u << 20);
+  if (!sane) c = make_int4(0, 0, 0, 0);
+  const int bx = c.w * S - 1, by = c.z * S - 1, bz = c.y * S - 1;
+#pragma unroll
+  for (int kz = 0; kz < 3; ++kz) {
+    const int iz = bz + kz;
+#pragma unroll
+    for (int ky = 0; ky < 3; ++ky) {
+      const int iy = by + ky;
+      const bool row_ok = (iz >= 0) && (iz < gz) && (iy >= 0) && (iy < gy);
+      const uint64_t row = (((uint64_t)c.x * gz + (uint64_t)(row_ok ? iz : 0)) * gy + (uint64_t)(row_ok ? iy : 0)) * gx;
+#pragma unroll
+      for (int kx = 0; kx < 3; ++kx) {
+        const int ix = bx + kx;
+        int32_t j = -1;
+        if (sane && row_ok && ix >= 0 && ix < gx) j = cell_lookup(in_idx, row + (uint64_t)ix);
+        if (j >= n_in) j = -1;  // only after a capacity overflow upstream
+        nbr[(int64_t)((kz * 3 + ky) * 3 + kx) * capacity_out + o] = j;
+      }
+    }
+  }
+}
+
+__global__ void k_copy_count(const int32_t* __restrict__ src, int32_t* __restrict__ dst, int64_t capacity,
+                             int32_t* __restrict__ d_flags) {
+  int32_t n = *src;
+  if (n > capacity) {
+    atomicOr(d_flags, EMC2_DEVFLAG_CAPACITY);
+    n = (int32_t)capacity;
+  }
+  *dst = n;
+}
+
+__global__ void __launch_bounds__(256) k_copy_coords(const int4* __restrict__ src, int4* __restrict__ dst,
+                                                     const int32_t* __restrict__ d_n, int64_t capacity) {
+  int64_t n = *d_n;
+  if (n > capacity) n = capacity;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+
+}  // namespace
+
+extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_in_coords,
+                                       const int32_t* d_n_in, int64_t capacity_in, const int32_t grid_in[3],
+                                       int32_t n_batch, int32_t in_slot, int32_t out_slot, int64_t capacity_out,
+                                       int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr, int32_t grid_out[3],
+                                       int32_t* h_n_out, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (kind != EMC2_CONV_SUBM && kind != EMC2_CONV_STRIDED)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: bad kind");
+  if (!d_in_coords || !d_n_in || !grid_in || !d_n_out || !d_nbr || !grid_out)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: null argument");
+  if (capacity_in < 1 || capacity_in > ctx->max_voxels || capacity_out < 1 || capacity_out > ctx->max_voxels)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: capacity outside [1, max_voxels]");
+  if (kind == EMC2_CONV_STRIDED && !d_out_coords)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: STRIDED needs d_out_coords");
+  int64_t cells_in = 0, cells_out = 0;
+  if (!emc2_grid_ok(grid_in, n_batch, &cells_in))
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_build_kmap: grid/batch out of the supported key range");
+  int32_t go[3];
+  for (int a = 0; a < 3; ++a) go[a] = kind == EMC2_CONV_SUBM ? grid_in[a] : (grid_in[a] - 1) / 2 + 1;
+  (void)emc2_grid_ok(go, n_batch, &cells_out);
+  if (cells_in > ctx->max_cells)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: %lld cells > max_cells %lld", (long long)cells_in,
+                     (long long)ctx->max_cells);
+  if (in_slot < -1 || in_slot >= ctx->n_slots || out_slot < -1 || out_slot >= ctx->n_slots)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: slot outside [-1, %d)", ctx->n_slots);
+  if (kind == EMC2_CONV_STRIDED && out_slot >= 0 && out_slot == in_slot)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: out_slot must differ from in_slot");
+  if (in_slot >= 0) {
+    const SlotMeta& m = ctx->meta[in_slot];
+    if (!m.valid || m.n_batch != n_batch || m.grid[0] != grid_in[0] || m.grid[1] != grid_in[1] || m.grid[2] != grid_in[2])
+      return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: in_slot %d does not hold an index for this grid", in_slot);
+  }
+  for (int a = 0; a < 3; ++a) grid_out[a] = go[a];
+
+  hipStream_t s = (hipStream_t)stream;
+  const int tmp_in = ctx->n_slots, tmp_out = ctx->n_slots + 1;
+  cellword_t* in_idx;
+  if (in_slot >= 0) {
+    in_idx = ctx->slots[in_slot];
+  } else {
+    // rebuild the input index from the (ascending, distinct) coordinates; ranks then equal positions
+    in_idx = ctx->slots[tmp_in];
+    emc2_index_clear(ctx, in_idx, cells_in, s);
+    emc2_index_mark_coords(ctx, in_idx, d_in_coords, d_n_in, capacity_in, grid_in, n_batch, s);
+    emc2_index_scan(ctx, in_idx, cells_in, capacity_in, ctx->dev_words + 2, s);
+  }
+
+  const int32_t* out_coords = d_in_coords;
+  if (kind == EMC2_CONV_SUBM) {
+    hipLaunchKernelGGL(k_copy_count, dim3(1), dim3(1), 0, s, d_n_in, d_n_out, capacity_out, ctx->dev_words);
+    if (d_out_coords && d_out_coords != d_in_coords) {
+      const int64_t m = capacity_in < capacity_out ? capacity_in : capacity_out;
+      hipLaunchKernelGGL(k_copy_coords, dim3((unsigned)emc2_div_up(m, 256)), dim3(256), 0, s, (const int4*)d_in_coords,
+                         (int4*)d_out_coords, d_n_out, m);
+    }
+    const int64_t m = capacity_in < capacity_out ? capacity_in : capacity_out;
+    hipLaunchKernelGGL(k_probe<1>, dim3((unsigned)emc2_div_up(m, 256)), dim3(256), 0, s, (const int4*)d_in_coords, d_n_out,
+                       capacity_out, in_idx, d_n_out, grid_in[0], grid_in[1], grid_in[2], n_batch, d_nbr);
+  } else {
+    cellword_t* out_idx = ctx->slots[out_slot >= 0 ? out_slot : tmp_out];
+    if (out_slot >= 0) {
+      SlotMeta& m = ctx->meta[out_slot];
+      for (int a = 0; a < 3; ++a) m.grid[a] = go[a];
+      m.n_batch = n_batch;
+      m.valid = true;
+    }
+    emc2_index_clear(ctx, out_idx, cells_out, s);
+    hipLaunchKernelGGL(k_strided_mark, dim3((unsigned)emc2_div_up(capacity_in, 256)), dim3(256), 0, s,
+                       (const int4*)d_in_coords, d_n_in, capacity_in, out_idx, go[0], go[1], go[2], grid_in[0], grid_in[1],
+                       grid_in[2], n_batch);
+    emc2_index_scan(ctx, out_idx, cells_out, capacity_out, d_n_out, s);
+    const int64_t n_words = emc2_div_up(cells_out, 32);
+    hipLaunchKernelGGL(k_expand_coords, dim3((unsigned)emc2_div_up(n_words, 256)), dim3(256), 0, s, out_idx, n_words,
+                       capacity_out, go[0], go[1], go[2], (int4*)d_out_coords);
+    out_coords = d_out_coords;
+    hipLaunchKernelGGL(k_probe<2>, dim3((unsigned)emc2_div_up(capacity_out, 256)), dim3(256), 0, s, (const int4*)out_coords,
+                       d_n_out, capacity_out, in_idx, d_n_in, grid_in[0], grid_in[1], grid_in[2], n_batch, d_nbr);
+  }
+  emc2_status st = emc2_check_hip(ctx, hipGetLastError(), "emc2_build_kmap launch");
+  if (st != EMC2_OK) return st;
+  if (h_n_out) {
+    st = emc2_check_hip(ctx, hipMemcpyAsync(ctx->pinned + 2, d_n_out, sizeof(int32_t), hipMemcpyDeviceToHost, s),
+                        "hipMemcpyAsync(n_out)");
+    if (st != EMC2_OK) return st;
+    st = emc2_check_hip(ctx, hipStreamSynchronize(s), "hipStreamSynchronize");
+    if (st != EMC2_OK) return st;
+    *h_n_out = ctx->pinned[2];
+  }
+  return EMC2_OK;
+}

@@ -1,0 +1,85 @@
+// Sparse convolution over a kernel map (paper Sec. 3.5: customised 3D sparse convolution over the
+// non-empty voxels; Sec. 3.6: graph fusion -> affine + ReLU fused into the epilogue).
+// This file: argument checks, dispatch, and the vector-ALU kernel (fp32 path and channel counts
+// the MFMA kernels do not cover).  The MFMA gather-GEMM lives in spconv_mfma.hip.
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include "common.h"
+#include "spconv_mfma.h"
+
+namespace {
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(__half v) { return __half2float(v); }
+__device__ __forceinline__ float to_f32(__hip_bfloat16 v) { return __bfloat162float(v); }
+__device__ __forceinline__ void from_f32(float* p, float v) { *p = v; }
+__device__ __forceinline__ void from_f32(__half* p, float v) { *p = __float2half_rn(v); }
+__device__ __forceinline__ void from_f32(__hip_bfloat16* p, float v) { *p = __float2bfloat16(v); }
+
+// Output-stationary: `cout` consecutive threads own one output row; taps outer, input channels inner.
+template <typename T>
+__global__ void __launch_bounds__(256) k_spconv_alu(const T* __restrict__ in, const T* __restrict__ w,
+                                                    const float* __restrict__ scale, const float* __restrict__ shift,
+                                                    int epilogue, const int32_t* __restrict__ nbr,
+                                                    const int32_t* __restrict__ d_n_out, int64_t capacity_out, int cin,
+                                                    int cout, int rows_per_block, T* __restrict__ out) {
+  int64_t n = *d_n_out;
+  if (n > capacity_out) n = capacity_out;
+  const int row = threadIdx.x / cout;
+  const int d = threadIdx.x - row * cout;
+  const int64_t o = (int64_t)blockIdx.x * rows_per_block + row;
+  if (row >= rows_per_block || o >= n) return;
+  float acc = 0.f;
+  for (int k = 0; k < 27; ++k) {
+    const int32_t j = nbr[(int64_t)k * capacity_out + o];
+    if (j < 0) continue;
+    const T* xr = in + (int64_t)j * cin;
+    const T* wk = w + (int64_t)k * cin * cout + d;
+    for (int c = 0; c < cin; ++c) acc = fmaf(to_f32(xr[c]), to_f32(wk[(int64_t)c * cout]), acc);
+  }
+  if (epilogue != EMC2_EPI_NONE) acc = fmaf(acc, scale[d], shift[d]);
+  if (epilogue == EMC2_EPI_AFFINE_RELU) acc = acc > 0.f ? acc : 0.f;
+  from_f32(out + o * cout + d, acc);
+}
+
+template <typename T>
+void launch_alu(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
+                const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
+                hipStream_t s) {
+  const int rows = 256 / cout;
+  hipLaunchKernelGGL(k_spconv_alu<T>, dim3((unsigned)emc2_div_up(capacity_out, rows)), dim3(256), 0, s, (const T*)d_in,
+                     (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, rows, (T*)d_out);
+}
+
+}  // namespace
+
+extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
+                                   const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
+                                   const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t cin,
+                                   int32_t cout, void* d_out, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (!d_in || !d_w || !d_nbr || !d_n_out || !d_out)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: null argument");
+  if (epilogue != EMC2_EPI_NONE && epilogue != EMC2_EPI_AFFINE && epilogue != EMC2_EPI_AFFINE_RELU)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: bad epilogue");
+  if ((epilogue == EMC2_EPI_NONE) != (d_scale == nullptr) || (d_scale == nullptr) != (d_shift == nullptr))
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: scale/shift must be given iff the epilogue is affine");
+  if (capacity_out < 1) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: capacity_out < 1");
+  if (cin < 1 || cout < 1 || cin > 1024 || cout > 256)
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: channels outside Cin<=1024, Cout<=256");
+  if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16)
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: bad dtype");
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype != EMC2_F32 && emc2_spconv_mfma_supported(cin, cout)) {
+    emc2_spconv_mfma_launch(dtype, d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
+                            d_out, s);
+  } else if (dtype == EMC2_F32) {
+    launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+  } else if (dtype == EMC2_F16) {
+    launch_alu<__half>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+  } else {
+    launch_alu<__hip_bfloat16>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+  }
+  return emc2_check_hip(ctx, hipGetLastError(), "emc2_spconv launch");
+}

@@ -1,0 +1,13 @@
+// Internal interface of the MFMA sparse-conv kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "emc2.h"
+
+// true iff (cin, cout) is covered by an MFMA instantiation (16-bit dtypes only)
+bool emc2_spconv_mfma_supported(int cin, int cout);
+
+void emc2_spconv_mfma_launch(emc2_dtype dtype, const void* d_in, const void* d_w, const float* d_scale,
+                             const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
+                             int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream);

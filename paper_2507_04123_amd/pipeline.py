@@ -1,0 +1,144 @@
+"""Host-side sequencing of the C-ABI calls for one workload branch: voxelize -> kernel maps -> convs.
+
+Only call ordering and buffer ownership live here; all arithmetic is in the HIP library.  Buffers
+are allocated once in ``__init__`` (sized by capacity), ``run`` allocates nothing and never syncs
+with the host: voxel counts stay in device memory between calls.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import binding as B
+from .configs import Branch, Config, Layer, SUBM, STRIDED, F32, F16, BF16, EPI_NONE, out_grid
+from . import gen
+
+_TD = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
+
+
+def cells_of(grid: Sequence[int], n_batch: int) -> int:
+    return int(grid[0]) * int(grid[1]) * int(grid[2]) * int(n_batch)
+
+
+def default_capacities(branch: Branch, n_points: int) -> List[int]:
+    """Safe per-level voxel capacities: L0 <= points; a stride-2 level holds at most 8x its input
+    and at most every cell of its grid."""
+    caps = [min(n_points, cells_of(branch.spec.grid, branch.spec.n_batch))]
+    grid = branch.spec.grid
+    for layer in branch.layers:
+        if layer.kind == STRIDED:
+            grid = out_grid(grid)
+            caps.append(min(8 * caps[-1], cells_of(grid, branch.spec.n_batch)))
+    return caps
+
+
+def device_params(layers: Sequence[Layer], seed: int, dtype: int, device: str = "cuda") -> List[Dict[str, torch.Tensor]]:
+    """Seeded weights / folded-BN parameters of a layer stack, rounded to `dtype`, on the device."""
+    out = []
+    for li, layer in enumerate(layers):
+        p = gen.make_layer_params(layer, seed, li)
+        out.append({
+            "w": torch.from_numpy(p["w"]).to(device).to(_TD[dtype]).contiguous(),
+            "scale": torch.from_numpy(p["scale"]).to(device),
+            "shift": torch.from_numpy(p["shift"]).to(device),
+        })
+    return out
+
+
+@dataclass
+class Level:
+    grid: Tuple[int, int, int]
+    cap: int
+    slot: int
+    coords: torch.Tensor          # [cap][4] i32
+    n: torch.Tensor               # [1] i32 (device count)
+    subm_nbr: Optional[torch.Tensor] = None   # [27][cap] i32, built lazily once per run
+    down_nbr: Optional[torch.Tensor] = None   # map from the previous level into this one
+
+
+class BranchRunner:
+    """Runs one Branch (one voxelization + its conv stack) through the library."""
+
+    def __init__(self, ctx: B.Context, branch: Branch, dtype: int, n_points: int, params: List[Dict[str, torch.Tensor]],
+                 capacities: Optional[Sequence[int]] = None, slot_base: int = 0, device: str = "cuda"):
+        self.ctx, self.branch, self.dtype = ctx, branch, dtype
+        self.params = params
+        caps = list(capacities) if capacities is not None else default_capacities(branch, n_points)
+        self.levels: List[Level] = []
+        grid = tuple(branch.spec.grid)
+        i32 = dict(dtype=torch.int32, device=device)
+        lvl = 0
+        self.levels.append(Level(grid, caps[0], slot_base, torch.empty((caps[0], 4), **i32), torch.zeros(1, **i32)))
+        need_subm = [False]
+        for layer in branch.layers:
+            if layer.kind == STRIDED:
+                lvl += 1
+                grid = out_grid(grid)
+                self.levels.append(Level(grid, caps[lvl], slot_base + lvl, torch.empty((caps[lvl], 4), **i32),
+                                         torch.zeros(1, **i32)))
+                self.levels[lvl].down_nbr = torch.empty((27, caps[lvl]), **i32)
+                need_subm.append(False)
+            else:
+                need_subm[lvl] = True
+        for lv, need in zip(self.levels, need_subm):
+            if need:
+                lv.subm_nbr = torch.empty((27, lv.cap), **i32)
+        self.n_slots = len(self.levels)
+        c0 = caps[0]
+        self.feats32 = torch.empty((c0, 4), dtype=torch.float32, device=device)
+        self.counts = torch.empty((c0,), dtype=torch.int32, device=device)
+        self.feats_lp = torch.empty((c0, 4), dtype=_TD[dtype], device=device) if dtype != F32 else None
+        # one activation buffer per layer output
+        self.acts: List[torch.Tensor] = []
+        lvl = 0
+        for layer in branch.layers:
+            if layer.kind == STRIDED:
+                lvl += 1
+            self.acts.append(torch.empty((self.levels[lvl].cap, layer.cout), dtype=_TD[dtype], device=device))
+
+    def run(self, points: torch.Tensor, batch: Optional[torch.Tensor]) -> torch.Tensor:
+        ctx, br = self.ctx, self.branch
+        l0 = self.levels[0]
+        ctx.voxelize(points, batch, br.spec, l0.cap, l0.coords, self.feats32, self.counts, l0.n,
+                     feats_lp=self.feats_lp, index_slot=l0.slot)
+        x = self.feats32 if self.dtype == F32 else self.feats_lp
+        lvl = 0
+        built = [False] * len(self.levels)
+        nb = br.spec.n_batch
+        for li, layer in enumerate(br.layers):
+            p = self.params[li]
+            has_epi = layer.epilogue != EPI_NONE
+            if layer.kind == STRIDED:
+                src, dst = self.levels[lvl], self.levels[lvl + 1]
+                ctx.build_kmap(B.STRIDED, src.coords, src.n, src.cap, src.grid, nb, dst.cap, dst.down_nbr, dst.n,
+                               out_coords=dst.coords, in_slot=src.slot, out_slot=dst.slot)
+                lvl += 1
+                nbr, lv = dst.down_nbr, dst
+            else:
+                lv = self.levels[lvl]
+                if not built[lvl]:
+                    ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n,
+                                   in_slot=lv.slot)
+                    built[lvl] = True
+                nbr = lv.subm_nbr
+            y = self.acts[li]
+            ctx.spconv(self.dtype, x, p["w"], p["scale"] if has_epi else None, p["shift"] if has_epi else None,
+                       layer.epilogue, nbr, lv.n, lv.cap, y)
+            x = y
+        return x
+
+
+def make_context_for(cfg: Config, capacities: Optional[Dict[str, Sequence[int]]] = None) -> Tuple[B.Context, int]:
+    """Context sized for every branch of a config: returns (ctx, total points)."""
+    n_points = cfg.n_points * cfg.n_frames
+    max_cells = max(cells_of(b.spec.grid, b.spec.n_batch) for b in cfg.branches)
+    max_vox = 1
+    n_slots = 1
+    for b in cfg.branches:
+        caps = capacities[b.name] if capacities and b.name in capacities else default_capacities(b, n_points)
+        max_vox = max(max_vox, max(caps))
+        n_slots = max(n_slots, len(caps))
+    return B.Context(n_points, max_vox, max_cells, n_slots=n_slots), n_points

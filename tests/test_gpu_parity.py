@@ -1,0 +1,446 @@
+"""GPU parity: the HIP path (through the C-ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: coordinates, counts and kernel maps bit-exact; features within rtol 1e-5 (fp32 path) or 2e-2
+(fp16/bf16 path against the fp32 oracle), measured as |g - o| <= rtol * (|o| + rms(o)).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import assert_features_close, layer_params_host, oracle_branch
+from paper_2507_04123_amd import binding as B
+from paper_2507_04123_amd import gen
+from paper_2507_04123_amd.configs import (CONFIGS, get_config, VoxelSpec, Branch, Layer, SUBM, STRIDED, F32, F16, BF16,
+                                          EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU, out_grid)
+from paper_2507_04123_amd.pipeline import BranchRunner, cells_of, default_capacities, device_params
+
+pytestmark = pytest.mark.gpu
+
+TD = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
+RTOL = {F32: 1e-5, F16: 2e-2, BF16: 2e-2}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _threads():
+    oracle.set_threads(min(16, oracle.max_threads()))
+    yield
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t if dtype is None else t.to(dtype)
+
+
+def gpu_voxelize(ctx, pts, batch, spec, cap, lp=None, slot=0):
+    coords = torch.full((cap, 4), -7, dtype=torch.int32, device="cuda")
+    feats = torch.zeros((cap, 4), dtype=torch.float32, device="cuda")
+    counts = torch.zeros((cap,), dtype=torch.int32, device="cuda")
+    n = torch.zeros(1, dtype=torch.int32, device="cuda")
+    flp = torch.zeros((cap, 4), dtype=lp, device="cuda") if lp is not None else None
+    nv = ctx.voxelize(dev(pts), None if batch is None else dev(batch), spec, cap, coords, feats, counts, n,
+                      feats_lp=flp, index_slot=slot, sync_count=True)
+    assert nv == int(n.item())
+    return coords, feats, counts, n, flp, nv
+
+
+def check_voxelize(ctx, pts, batch, spec, cap, lp=torch.float16):
+    print(f"voxelize P={len(pts)} grid={spec.grid} B={spec.n_batch}", flush=True)
+    coords, feats, counts, n, flp, nv = gpu_voxelize(ctx, pts, batch, spec, cap, lp)
+    ctx.status_sync()
+    oc, om, on = oracle.voxelize(pts, batch, spec.lo, spec.vs, spec.grid, spec.n_batch, spec.r2_min, spec.r2_max)
+    assert nv == len(oc)
+    assert np.array_equal(coords[:nv].cpu().numpy(), oc)
+    assert np.array_equal(counts[:nv].cpu().numpy(), on)
+    assert_features_close(feats[:nv].cpu().numpy(), om, 1e-5, "voxel means")
+    if flp is not None:
+        assert_features_close(flp[:nv].float().cpu().numpy(), om, 2e-3, "16-bit voxel means")
+    return coords, feats, counts, n, flp, nv, (oc, om, on)
+
+
+# ------------------------------------------------------------------------------------------------
+# voxelize
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("cfg_index", [1, 2, 3, 4, 5])
+def test_voxelize_all_configs_full_size(cfg_index):
+    cfg = get_config(cfg_index)
+    pts, batch = gen.make_frames(cfg)
+    if cfg.n_frames == 1:
+        batch = None
+    max_cells = max(cells_of(b.spec.grid, b.spec.n_batch) for b in cfg.branches)
+    ctx = B.Context(len(pts), len(pts), max_cells, n_slots=1)
+    for br in cfg.branches:
+        check_voxelize(ctx, pts, batch, br.spec, len(pts))
+    ctx.close()
+
+
+def test_voxelize_edge_cases():
+    spec = VoxelSpec((0.0, 0.0, 0.0), (0.5, 0.5, 0.5), (8, 8, 8))
+    ctx = B.Context(5000, 5000, 8 * 8 * 8 * 4, n_slots=2)
+    # empty input
+    coords, feats, counts, n, _, nv = gpu_voxelize(ctx, np.zeros((0, 4), np.float32), None, spec, 16)
+    assert nv == 0
+    # every point dropped (outside / NaN / inf)
+    bad = np.array([[-1, 1, 1, 0], [1, 9, 1, 0], [np.nan, 1, 1, 0], [1, 1, np.inf, 0], [1, 1, 1, np.nan],
+                    [4.0, 1, 1, 0.5]], np.float32)
+    bad[-1, 0] = 4.0                                      # x = 4.0 -> t = 8.0 = G: dropped
+    assert gpu_voxelize(ctx, bad, None, spec, 16)[5] == 0
+    # all points in one voxel (maximum contention on one hash record)
+    st = gen.Stream(5)
+    one = np.stack([st.uniform(4096, 1.0, 1.45), st.uniform(4096, 2.0, 2.45), st.uniform(4096, 3.0, 3.45),
+                    st.uniform(4096)], axis=1).astype(np.float32)
+    c, f, k, _, _, nv, _ = check_voxelize(ctx, one, None, spec, 16)
+    assert nv == 1 and int(k[0]) == 4096
+    # fully occupied grid, several frames, wide rows (stride_f = 6), ragged tail sizes
+    spec4 = VoxelSpec((0.0, 0.0, 0.0), (0.5, 0.5, 0.5), (8, 8, 8), n_batch=4)
+    st = gen.Stream(6)
+    pts = np.concatenate([np.stack([st.uniform(4999, 0, 4), st.uniform(4999, 0, 4), st.uniform(4999, 0, 4),
+                                    st.uniform(4999)], axis=1), np.ones((4999, 2))], axis=1).astype(np.float32)
+    batch = (st.bits(4999) % np.uint64(5)).astype(np.int32) - 0   # ids 0..4: id 4 is out of range
+    check_voxelize(ctx, pts, batch, spec4, 4999)
+    # capacity too small -> device status says so, outputs stay in bounds
+    coords, feats, counts, n, _, nv = gpu_voxelize(ctx, pts, batch, spec4, 100)
+    assert nv == 100
+    with pytest.raises(B.Emc2Error) as e:
+        ctx.status_sync()
+    assert e.value.status == B.ERR_CAPACITY
+    ctx.status_sync()                                       # cleared
+    # host-side argument errors
+    with pytest.raises(B.Emc2Error):
+        gpu_voxelize(ctx, pts, batch, spec4, 100000)        # capacity > max_voxels
+    with pytest.raises(B.Emc2Error):
+        gpu_voxelize(ctx, pts, batch, VoxelSpec((0, 0, 0), (0.5, 0.5, 0.5), (64, 64, 64)), 100)   # > max_cells
+    ctx.close()
+
+
+def test_voxelize_repeat_runs_and_permutation_are_bit_identical_in_coords():
+    cfg = get_config(2)
+    pts, _ = gen.make_frames(cfg)
+    spec = cfg.branches[0].spec
+    ctx = B.Context(len(pts), len(pts), cells_of(spec.grid, 1), n_slots=1)
+    c0, f0, k0, _, _, n0 = gpu_voxelize(ctx, pts, None, spec, len(pts))
+    c1, f1, k1, _, _, n1 = gpu_voxelize(ctx, pts, None, spec, len(pts))
+    perm = gen.Stream(77).permutation(len(pts))
+    c2, f2, k2, _, _, n2 = gpu_voxelize(ctx, pts[perm], None, spec, len(pts))
+    assert n0 == n1 == n2
+    assert torch.equal(c0[:n0], c1[:n0]) and torch.equal(c0[:n0], c2[:n0])
+    assert torch.equal(k0[:n0], k1[:n0]) and torch.equal(k0[:n0], k2[:n0])
+    assert_features_close(f2[:n0].cpu().numpy(), f0[:n0].cpu().numpy(), 1e-5, "means under permutation")
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# kernel maps
+# ------------------------------------------------------------------------------------------------
+
+def gpu_kmap(ctx, kind, coords_t, n_t, cap_in, grid, nb, cap_out, in_slot=-1, out_slot=-1):
+    nbr = torch.full((27, cap_out), -9, dtype=torch.int32, device="cuda")
+    n_out = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out_coords = torch.full((cap_out, 4), -7, dtype=torch.int32, device="cuda") if kind == STRIDED else None
+    gout, nv = ctx.build_kmap(kind, coords_t, n_t, cap_in, grid, nb, cap_out, nbr, n_out, out_coords=out_coords,
+                              in_slot=in_slot, out_slot=out_slot, sync_count=True)
+    return nbr, n_out, out_coords, gout, nv
+
+
+def check_kmap_chain(ctx, coords_np, grid, nb, n_levels, use_slots, cap_slack=1.0):
+    """SUBM map at every level and the STRIDED map between levels, against the oracle."""
+    n = len(coords_np)
+    cap = max(int(n * cap_slack) + 3, 1)
+    coords_t = torch.zeros((cap, 4), dtype=torch.int32, device="cuda")
+    coords_t[:n] = dev(coords_np)
+    n_t = torch.tensor([n], dtype=torch.int32, device="cuda")
+    slot = -1
+    if use_slots:                                   # leave a valid index in slot 0 via the rebuild path of a STRIDED call
+        slot = 0
+    cur_np, cur_t, cur_n, cur_cap, cur_grid = coords_np, coords_t, n_t, cap, tuple(grid)
+    have_slot = False
+    for lvl in range(n_levels):
+        print(f"kmap level {lvl} V={len(cur_np)} grid={cur_grid}", flush=True)
+        in_slot = lvl if (use_slots and have_slot) else -1
+        nbr, n_out, _, gout, nv = gpu_kmap(ctx, SUBM, cur_t, cur_n, cur_cap, cur_grid, nb, cur_cap, in_slot=in_slot)
+        _, o_nbr, _ = oracle.build_kmap(0, cur_np, cur_grid, nb)
+        assert nv == len(cur_np) and gout == cur_grid
+        assert np.array_equal(nbr[:, :nv].cpu().numpy(), o_nbr)
+        if lvl == n_levels - 1:
+            break
+        o_out, o_dn, o_g = oracle.build_kmap(1, cur_np, cur_grid, nb)
+        cap_out = max(int(len(o_out) * cap_slack) + 5, 1)
+        nbr, n_out, out_coords, gout, nv = gpu_kmap(ctx, STRIDED, cur_t, cur_n, cur_cap, cur_grid, nb, cap_out,
+                                                    in_slot=in_slot, out_slot=(lvl + 1) if use_slots else -1)
+        assert gout == o_g and nv == len(o_out)
+        assert np.array_equal(out_coords[:nv].cpu().numpy(), o_out)
+        assert np.array_equal(nbr[:, :nv].cpu().numpy(), o_dn)
+        cur_np, cur_t, cur_n, cur_cap, cur_grid = o_out, out_coords, n_out, cap_out, o_g
+        have_slot = use_slots
+    ctx.status_sync()
+
+
+def _rand_sites(seed, grid, nb, n):
+    gx, gy, gz = grid
+    total = gx * gy * gz * nb
+    keys = np.unique((gen.Stream(seed, 3).bits(3 * n) % np.uint64(total)).astype(np.int64))[:n]
+    keys.sort()
+    x = keys % gx; y = (keys // gx) % gy; z = (keys // (gx * gy)) % gz; b = keys // (gx * gy * gz)
+    return np.stack([b, z, y, x], axis=1).astype(np.int32)
+
+
+@pytest.mark.parametrize("use_slots", [False, True])
+def test_kmap_small_random_grids(use_slots):
+    ctx = B.Context(1000, 60000, 40 * 33 * 21 * 3, n_slots=4)
+    for seed, grid, nb, n in [(1, (40, 33, 21), 3, 5000), (2, (9, 8, 5), 2, 300), (3, (17, 21, 11), 1, 40),
+                              (4, (1, 1, 1), 1, 1), (5, (33, 2, 1), 1, 50), (6, (6, 6, 6), 2, 432)]:
+        coords = _rand_sites(seed, grid, nb, n)
+        check_kmap_chain(ctx, coords, grid, nb, 3, use_slots, cap_slack=1.3)
+    # empty input
+    z = torch.zeros((4, 4), dtype=torch.int32, device="cuda")
+    n0 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    nbr, n_out, oc, gout, nv = gpu_kmap(ctx, STRIDED, z, n0, 4, (8, 8, 8), 1, 4)
+    assert nv == 0 and gout == (4, 4, 4)
+    nbr, n_out, oc, gout, nv = gpu_kmap(ctx, SUBM, z, n0, 4, (8, 8, 8), 1, 4)
+    assert nv == 0
+    ctx.close()
+
+
+def test_kmap_capacity_overflow_is_reported():
+    ctx = B.Context(1000, 5000, 20 * 20 * 20, n_slots=2)
+    coords = _rand_sites(9, (20, 20, 20), 1, 800)
+    t = dev(coords)
+    n_t = torch.tensor([len(coords)], dtype=torch.int32, device="cuda")
+    nbr, n_out, oc, gout, nv = gpu_kmap(ctx, STRIDED, t, n_t, len(coords), (20, 20, 20), 1, 50)
+    assert nv == 50
+    with pytest.raises(B.Emc2Error) as e:
+        ctx.status_sync()
+    assert e.value.status == B.ERR_CAPACITY
+    assert int(nbr[:, :50].max()) < len(coords)
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg_index", [1, 2, 4, 5])
+def test_kmap_configs_full_size(cfg_index):
+    cfg = get_config(cfg_index)
+    pts, batch = gen.make_frames(cfg)
+    if cfg.n_frames == 1:
+        batch = None
+    for br in cfg.branches:
+        sp = br.spec
+        n_levels = 1 + sum(1 for l in br.layers if l.kind == STRIDED)
+        oc, _, _ = oracle.voxelize(pts, batch, sp.lo, sp.vs, sp.grid, sp.n_batch, sp.r2_min, sp.r2_max)
+        caps = default_capacities(br, len(pts))
+        ctx = B.Context(len(pts), max(caps), cells_of(sp.grid, sp.n_batch), n_slots=n_levels)
+        check_kmap_chain(ctx, oc, sp.grid, sp.n_batch, n_levels, use_slots=True)
+        ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# sparse conv
+# ------------------------------------------------------------------------------------------------
+
+def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None):
+    n_out = nbr_np.shape[1]
+    cap = cap or max(n_out, 1)
+    nbr = torch.full((27, cap), -1, dtype=torch.int32, device="cuda")
+    nbr[:, :n_out] = dev(nbr_np)
+    x = dev(x_np, TD[dtype]) if len(x_np) else torch.zeros((1, x_np.shape[1]), dtype=TD[dtype], device="cuda")
+    w = dev(w_np, TD[dtype])
+    out = torch.full((cap, w_np.shape[2]), 768.0, dtype=TD[dtype], device="cuda")
+    n_t = torch.tensor([n_out], dtype=torch.int32, device="cuda")
+    ctx.spconv(dtype, x, w, None if scale is None else dev(scale), None if shift is None else dev(shift), epi, nbr, n_t,
+               cap, out)
+    torch.cuda.synchronize()
+    return out
+
+
+CONV_CASES = [
+    # dtype, cin, cout, grid, n_sites, epilogue
+    (F32, 4, 16, (30, 30, 10), 3000, EPI_NONE),
+    (F32, 5, 7, (12, 9, 7), 500, EPI_AFFINE_RELU),
+    (F32, 16, 32, (20, 20, 8), 2500, EPI_AFFINE),
+    (F16, 4, 16, (30, 30, 10), 3000, EPI_AFFINE_RELU),
+    (F16, 16, 16, (30, 30, 10), 3000, EPI_AFFINE_RELU),
+    (F16, 16, 32, (24, 24, 8), 3333, EPI_AFFINE_RELU),
+    (F16, 32, 32, (24, 24, 8), 3333, EPI_AFFINE_RELU),
+    (F16, 32, 64, (24, 24, 8), 1111, EPI_AFFINE),
+    (F16, 64, 64, (16, 16, 8), 1500, EPI_AFFINE_RELU),
+    (F16, 64, 64, (16, 16, 8), 1500, EPI_NONE),
+    (F16, 64, 128, (16, 16, 8), 1027, EPI_AFFINE_RELU),
+    (F16, 128, 128, (16, 16, 8), 777, EPI_AFFINE_RELU),
+    (BF16, 64, 64, (16, 16, 8), 1500, EPI_AFFINE_RELU),
+    (BF16, 16, 32, (24, 24, 8), 999, EPI_AFFINE_RELU),
+    (BF16, 4, 32, (24, 24, 8), 999, EPI_AFFINE_RELU),
+]
+
+
+@pytest.mark.parametrize("dtype,cin,cout,grid,n,epi", CONV_CASES)
+def test_spconv_subm_and_strided_small(dtype, cin, cout, grid, n, epi):
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    coords = _rand_sites(cin * 1000 + cout, grid, 1, n)
+    st = gen.Stream(cin * 7 + cout, 5)
+    x = gen.round_to_dtype(st.normal(len(coords) * cin).astype(np.float32).reshape(-1, cin), dtype)
+    w = gen.round_to_dtype(st.normal(27 * cin * cout, 0.1).astype(np.float32).reshape(27, cin, cout), dtype)
+    scale = (st.uniform(cout, 0.8, 1.2) / (0.1 * np.sqrt(9.0 * cin))).astype(np.float32) if epi != EPI_NONE else None
+    shift = st.uniform(cout, -0.1, 0.1).astype(np.float32) if epi != EPI_NONE else None
+    for kind in (SUBM, STRIDED):
+        _, nbr, _ = oracle.build_kmap(kind, coords, grid, 1)
+        print(f"spconv dtype={dtype} {cin}->{cout} kind={kind} n_out={nbr.shape[1]} epi={epi}", flush=True)
+        exp = oracle.spconv(x, w, scale, shift, epi, nbr)
+        cap = nbr.shape[1] + 37                                  # capacity beyond n_out: tail must stay untouched
+        got = gpu_spconv(ctx, dtype, x, w, scale, shift, epi, nbr, cap=cap)
+        assert_features_close(got[:nbr.shape[1]].float().cpu().numpy(), exp, RTOL[dtype], f"spconv {cin}->{cout}")
+        assert torch.all(got[nbr.shape[1]:].float() == 768.0)
+    ctx.close()
+
+
+def test_spconv_empty_and_all_absent():
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    w = np.zeros((27, 64, 64), np.float32)
+    got = gpu_spconv(ctx, F16, np.zeros((0, 64), np.float32), w, None, None, EPI_NONE, np.zeros((27, 0), np.int32), cap=8)
+    assert torch.all(got.float() == 768.0)
+    nbr = -np.ones((27, 100), np.int32)
+    shift = np.full(64, 0.25, np.float32)
+    got = gpu_spconv(ctx, F16, np.ones((3, 64), np.float32), w + 1, np.ones(64, np.float32), shift, EPI_AFFINE, nbr)
+    assert torch.all(got.float() == 0.25)                         # no neighbour at all: acc = 0 -> shift
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# projection + gather
+# ------------------------------------------------------------------------------------------------
+
+def check_project(ctx, pts, pm, img, margin=1e-3):
+    n, c = len(pts), img.shape[2]
+    out = torch.full((n, c), 5.0, dtype=torch.float16, device="cuda")
+    valid = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+    uv = torch.zeros((n, 2), dtype=torch.float32, device="cuda")
+    ctx.project_gather(dev(pts), pm, dev(img), out, valid, uv)
+    torch.cuda.synchronize()
+    eg, ev, euv = oracle.project_gather(pts, pm, img, want_uv=True)
+    h, w = img.shape[:2]
+    # points within `margin` px of a validity boundary may legitimately flip; count and exclude them
+    P = np.asarray(pm, np.float64).reshape(3, 4)
+    ww = P[2, 0] * pts[:, 0].astype(np.float64) + P[2, 1] * pts[:, 1] + P[2, 2] * pts[:, 2] + P[2, 3]
+    u, v = euv[:, 0], euv[:, 1]
+    with np.errstate(invalid="ignore"):
+        near = (np.abs(ww) < margin) | (np.abs(u) < margin) | (np.abs(u - (w - 1)) < margin) | (np.abs(v) < margin) | \
+               (np.abs(v - (h - 1)) < margin)
+    near &= np.isfinite(ww)
+    keep = ~near
+    assert near.mean() < 0.01
+    gv = valid.cpu().numpy()
+    assert np.array_equal(gv[keep], ev[keep])
+    g = out.float().cpu().numpy()
+    assert np.all(g[(gv == 0)] == 0.0)
+    assert_features_close(g[keep], eg[keep], 2e-3, "bilinear gather")       # one fp16 rounding of an O(1) blend
+    fin = np.isfinite(euv[:, 0]) & keep
+    np.testing.assert_allclose(uv.cpu().numpy()[fin], euv[fin], rtol=2e-6, atol=1e-4)
+    return int(ev.sum()), int(near.sum())
+
+
+def test_project_gather_config3_full_size():
+    cfg = get_config(3)
+    pts, _ = gen.make_frames(cfg)
+    cam = cfg.camera
+    pm = gen.make_camera(gen.frame_seed(3, 0))
+    img = gen.make_image(cam.height, cam.width, cam.channels, gen.frame_seed(3, 0))
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    n_valid, n_near = check_project(ctx, pts, pm, img)
+    print(f"project_gather: {n_valid} of {len(pts)} valid, {n_near} inside the exclusion band", flush=True)
+    assert n_valid > len(pts) // 20
+    ctx.close()
+
+
+def test_project_gather_edges():
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    img = gen.make_image(5, 6, 8, 3)
+    pm = [1, 0, 0, 0, 0, 1, 0, 0, 0, 0, 1, 0]
+    pts = np.array([[1, 1, -1, 0], [1, 1, 0, 0], [6, 1, 1, 0], [5, 4, 1, 0], [-0.01, 1, 1, 0], [1, 4.01, 1, 0],
+                    [np.nan, 1, 1, 0], [2.5, 1.5, 1, 0], [0, 0, 1, 0], [3, 2, 1, 0]], np.float32)
+    check_project(ctx, pts, pm, img, margin=0.0)              # exact inputs: both sides decide identically
+    st = gen.Stream(8)
+    many = np.stack([st.uniform(1003, -1, 7), st.uniform(1003, -1, 6), st.uniform(1003, 0.5, 1.5), st.uniform(1003),
+                     st.uniform(1003)], axis=1).astype(np.float32)          # stride_f = 5
+    check_project(ctx, many, pm, gen.make_image(5, 6, 64, 4))
+    out = torch.zeros((0, 8), dtype=torch.float16, device="cuda")
+    ctx.project_gather(torch.zeros((0, 4), device="cuda"), pm, dev(img), out, torch.zeros(0, dtype=torch.uint8, device="cuda"))
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# whole configurations: chained path, per-layer check with the oracle fed the GPU's own inputs
+# ------------------------------------------------------------------------------------------------
+
+def run_config_branch(cfg, br, pts, batch, full_chain, n_sample=1500):
+    sp = br.spec
+    caps = default_capacities(br, len(pts))
+    ctx = B.Context(len(pts), max(caps), cells_of(sp.grid, sp.n_batch), n_slots=len(caps))
+    seed = gen.frame_seed(cfg.index, 0) + len(br.name)
+    params = device_params(br.layers, seed, cfg.dtype)
+    hparams = layer_params_host(br, seed, cfg.dtype)
+    runner = BranchRunner(ctx, br, cfg.dtype, len(pts), params, capacities=caps)
+    print(f"config {cfg.index} branch {br.name}: P={len(pts)} caps={caps}", flush=True)
+    y = runner.run(dev(pts), None if batch is None else dev(batch))
+    ctx.status_sync()
+    rtol = RTOL[cfg.dtype]
+    # integer parts, every level
+    oc, om, on = oracle.voxelize(pts, batch, sp.lo, sp.vs, sp.grid, sp.n_batch, sp.r2_min, sp.r2_max)
+    n0 = int(runner.levels[0].n.item())
+    assert n0 == len(oc) and np.array_equal(runner.levels[0].coords[:n0].cpu().numpy(), oc)
+    x_in = (runner.feats32 if cfg.dtype == F32 else runner.feats_lp)[:n0].float().cpu().numpy()
+    cur_coords, cur_grid, lvl = oc, tuple(sp.grid), 0
+    subm_cache = {}
+    st = gen.Stream(1234, cfg.index)
+    for li, layer in enumerate(br.layers):
+        if layer.kind == STRIDED:
+            o_out, o_nbr, o_g = oracle.build_kmap(1, cur_coords, cur_grid, sp.n_batch)
+            lvl += 1
+            lv = runner.levels[lvl]
+            nv = int(lv.n.item())
+            assert nv == len(o_out) and np.array_equal(lv.coords[:nv].cpu().numpy(), o_out)
+            assert np.array_equal(lv.down_nbr[:, :nv].cpu().numpy(), o_nbr)
+            cur_coords, cur_grid, nbr = o_out, o_g, o_nbr
+        else:
+            if lvl not in subm_cache:
+                _, subm_cache[lvl], _ = oracle.build_kmap(0, cur_coords, cur_grid, sp.n_batch)
+                nv = len(cur_coords)
+                assert np.array_equal(runner.levels[lvl].subm_nbr[:, :nv].cpu().numpy(), subm_cache[lvl])
+            nbr = subm_cache[lvl]
+        n_out = nbr.shape[1]
+        got = runner.acts[li][:n_out].float().cpu().numpy()
+        # (i) this layer alone: oracle on the GPU's own input activations, on a sample of outputs
+        if n_out > n_sample:
+            sel = np.sort(st.permutation(n_out)[:n_sample])
+        else:
+            sel = np.arange(n_out)
+        p = hparams[li]
+        epi = layer.epilogue
+        exp = oracle.spconv(x_in, p["w"], p["scale"] if epi != EPI_NONE else None, p["shift"] if epi != EPI_NONE else None,
+                            epi, np.ascontiguousarray(nbr[:, sel]))
+        assert_features_close(got[sel], exp, rtol, f"cfg{cfg.index}/{br.name} layer {li} ({layer.cin}->{layer.cout})")
+        assert float(np.abs(got).max()) < 3e4
+        x_in = got
+    if full_chain:
+        # (ii) end to end against the fp32-activation oracle chain
+        ob = oracle_branch(pts, batch, br, cfg.dtype, hparams)
+        final = ob["acts"][-1]
+        assert_features_close(x_in, final, rtol * (1.0 if cfg.dtype == F32 else 2.0), f"cfg{cfg.index}/{br.name} end-to-end")
+    ctx.close()
+
+
+@pytest.mark.parametrize("cfg_index,full_chain", [(1, True), (2, True), (3, True), (4, False), (5, False)])
+def test_config_pipeline(cfg_index, full_chain):
+    cfg = get_config(cfg_index)
+    pts, batch = gen.make_frames(cfg)
+    if cfg.n_frames == 1:
+        batch = None
+    for br in cfg.branches:
+        run_config_branch(cfg, br, pts, batch, full_chain)
+
+
+def test_config4_and_5_reduced_end_to_end():
+    """Configs 4 and 5 with a quarter of the points, so the full fp32 oracle chain stays affordable."""
+    for idx in (4, 5):
+        cfg = get_config(idx)
+        pts, batch = gen.make_frames(cfg)
+        pts, batch = pts[::4].copy(), batch[::4].copy()
+        for br in cfg.branches:
+            run_config_branch(cfg, br, pts, batch if cfg.n_frames > 1 else None, True)

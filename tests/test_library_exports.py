@@ -1,0 +1,43 @@
+"""The C-ABI library loads and exports every function include/emc2.h declares (no compute calls)."""
+import ctypes
+import os
+import re
+
+from paper_2507_04123_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "emc2.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(emc2_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported():
+    names = _declared_functions()
+    assert {"emc2_voxelize", "emc2_build_kmap", "emc2_spconv", "emc2_project_gather"} <= set(names)
+    lib = ctypes.CDLL(binding.LIB_PATH)          # raises if the library is not built
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in emc2.h but not exported"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_product_does_not_import_the_oracle():
+    """The product package must never route through the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2507_04123_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src and "emc2o" not in src, f
+
+
+def test_invalid_arguments_are_rejected_without_a_gpu_call():
+    lib = binding.load_library()
+    h = ctypes.c_void_p()
+    assert lib.emc2_create(None, 0, 10, 10, 10, 1) == binding.ERR_INVALID_ARG
+    assert lib.emc2_create(ctypes.byref(h), 0, 0, 10, 10, 1) == binding.ERR_INVALID_ARG
+    assert lib.emc2_create(ctypes.byref(h), 0, 10, 10, 10, 0) == binding.ERR_INVALID_ARG
+    assert lib.emc2_status_sync(None, None) == binding.ERR_INVALID_ARG
+    assert lib.emc2_last_error(None) == b"null context"
