@@ -1,0 +1,210 @@
+#!/usr/bin/env python3
+"""Bench: frames/s through voxelize + kernel maps + sparse-conv backbone on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic frame of the front-view 64-beam
+workload (120k points, fp16 SECOND-style backbone: 1 voxelization, 7 kernel maps, 10 convs), with
+the points already resident in HBM.  Prints ONE JSON line with the throughput, a `roofline` object
+for the dominant kernel (timed live with stream events inside the timed steps) and a `cpu_baseline`
+object (the CPU oracle timed on this machine's host cores on one frame).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F16_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E, published
+
+
+class EventTimer:
+    """Brackets library calls with events on the stream they are launched on (torch's current stream)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.records = []           # (tag, start_event, stop_event)
+        self.enabled = False
+
+    def __call__(self, tag):
+        return _Span(self, tag)
+
+    def reset(self):
+        self.records = []
+
+
+class _Span:
+    def __init__(self, timer, tag):
+        self.t, self.tag = timer, tag
+
+    def __enter__(self):
+        if self.t.enabled:
+            self.e0 = self.t.torch.cuda.Event(enable_timing=True)
+            self.e1 = self.t.torch.cuda.Event(enable_timing=True)
+            self.e0.record()
+        return self
+
+    def __exit__(self, *a):
+        if self.t.enabled:
+            self.e1.record()
+            self.t.records.append((self.tag, self.e0, self.e1))
+        return False
+
+
+def cpu_baseline(cfg, pts, seed, threads):
+    """The oracle as it stands, on one full frame of the same workload, all stages."""
+    import oracle
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from helpers import layer_params_host, oracle_branch
+    oracle.set_threads(threads)
+    br = cfg.branches[0]
+    hp = layer_params_host(br, seed, cfg.dtype)
+    t0 = time.perf_counter()
+    oracle_branch(pts, None, br, cfg.dtype, hp)
+    dt = time.perf_counter() - t0
+    return {"value": 1.0 / dt, "unit": "frames/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 full frame of {cfg.name} (voxelize + 7 kernel maps + 10 convs), {dt:.2f} s",
+            "ms_per_frame": dt * 1e3}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload index (2 = the metric's configuration)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tight-capacity", action="store_true",
+                    help="size per-level capacities from a calibration pass (x1.25) instead of the safe bounds")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (frames shard across GPUs with no "
+              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2507_04123_amd import binding as B
+    from paper_2507_04123_amd import gen
+    from paper_2507_04123_amd.configs import get_config, STRIDED
+    from paper_2507_04123_amd.pipeline import BranchRunner, cells_of, default_capacities, device_params
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = get_config(args.config)
+    assert len(cfg.branches) == 1, "bench covers single-branch backbones"
+    br = cfg.branches[0]
+    pts_np, batch_np = gen.make_frames(cfg)
+    seed = gen.frame_seed(cfg.index, 0)
+    pts = torch.from_numpy(pts_np).cuda()
+    batch = torch.from_numpy(batch_np).cuda() if cfg.n_frames > 1 else None
+    n_points = len(pts_np)
+
+    caps = default_capacities(br, n_points)
+
+    def make(caps_):
+        ctx_ = B.Context(n_points, max(caps_), cells_of(br.spec.grid, br.spec.n_batch), n_slots=len(caps_))
+        return ctx_, BranchRunner(ctx_, br, cfg.dtype, n_points, device_params(br.layers, seed, cfg.dtype), capacities=caps_)
+
+    ctx, runner = make(caps)
+    runner.run(pts, batch)
+    ctx.status_sync()
+    if args.tight_capacity:
+        counts = [int(lv.n.item()) for lv in runner.levels]
+        caps = [min(c, int(v * 1.25) + 256) for c, v in zip(caps, counts)]
+        ctx.close()
+        ctx, runner = make(caps)
+        runner.run(pts, batch)
+        ctx.status_sync()
+
+    # flop / byte accounting from the kernel maps of this frame (outside the timed region)
+    n_vox = [int(lv.n.item()) for lv in runner.levels]
+    layer_pairs, layer_flops = [], []
+    for li, layer in enumerate(br.layers):
+        nbr, lv = runner.layer_map(li)
+        n = int(lv.n.item())
+        pairs = int((nbr[:, :n] >= 0).sum().item())
+        layer_pairs.append(pairs)
+        layer_flops.append(2.0 * pairs * layer.cin * layer.cout)
+
+    timer = EventTimer(torch)
+    for _ in range(args.warmup):
+        runner.run(pts, batch, timer)
+    torch.cuda.synchronize()
+    timer.enabled = True
+    timer.reset()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        runner.run(pts, batch, timer)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ctx.status_sync()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    frames_per_s = cfg.n_frames * args.steps / (t1 - t0)
+
+    # per-call durations from the events recorded inside the timed steps
+    stage_ms = {}
+    conv_ms = [0.0] * len(br.layers)
+    for tag, e0, e1 in timer.records:
+        ms = e0.elapsed_time(e1)
+        if isinstance(tag, tuple):
+            conv_ms[tag[1]] += ms
+            stage_ms["conv"] = stage_ms.get("conv", 0.0) + ms
+        else:
+            stage_ms[tag] = stage_ms.get(tag, 0.0) + ms
+    stage_ms = {k: v / args.steps for k, v in stage_ms.items()}
+    conv_ms = [v / args.steps for v in conv_ms]
+
+    # group conv launches by kernel instantiation (cin, cout); the dominant one carries the roofline
+    groups = {}
+    for li, layer in enumerate(br.layers):
+        g = groups.setdefault((layer.cin, layer.cout), {"ms": 0.0, "flops": 0.0, "launches": 0})
+        g["ms"] += conv_ms[li]
+        g["flops"] += layer_flops[li]
+        g["launches"] += 1
+    dom_key = max(groups, key=lambda k: groups[k]["ms"])
+    dom = groups[dom_key]
+    achieved_tflops = dom["flops"] / (dom["ms"] * 1e-3) / 1e12 if dom["ms"] > 0 else 0.0
+    roofline = {
+        "kernel": f"k_spconv_mfma<f16, Cin={dom_key[0]}, Cout={dom_key[1]}>",
+        "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved_tflops / PEAK_MFMA_F16_TFLOPS,
+        "flops_per_launch": dom["flops"] / dom["launches"], "launches_per_step": dom["launches"],
+        "avg_launch_ms": dom["ms"] / dom["launches"],
+        "traffic": None,
+    }
+
+    total_flops = sum(layer_flops)
+    vox_ms = stage_ms.get("voxelize", 0.0)
+    out = {
+        "metric": "frames/s through voxelize+spconv backbone",
+        "value": frames_per_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"config {cfg.index} ({cfg.name}): {cfg.n_points} points x {cfg.n_frames} frame(s), "
+                               f"grid {br.spec.grid}, {len(br.layers)} sparse convs", "capacities": caps,
+                   "voxels_per_level": n_vox},
+        "roofline": roofline,
+        "stages_ms": stage_ms,
+        "voxelize_mpts_per_s": (n_points / (vox_ms * 1e-3) / 1e6) if vox_ms > 0 else None,
+        "conv_useful_gflop_per_frame": total_flops / 1e9,
+        "conv_useful_tflops": total_flops / (stage_ms.get("conv", 0.0) * 1e-3) / 1e12 if stage_ms.get("conv") else None,
+        "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m}
+                        for l, p, m in zip(br.layers, layer_pairs, conv_ms)],
+    }
+    ctx.close()
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = min(oracle.max_threads(), 16)
+        out["cpu_baseline"] = cpu_baseline(cfg, pts_np, seed, threads)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -48,6 +48,21 @@ def device_params(layers: Sequence[Layer], seed: int, dtype: int, device: str = 
     return out
 
 
+class _NoTimer:
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        return False
+
+
+_NO_TIMER = _NoTimer()
+
+
+def _no_timer(tag):
+    return _NO_TIMER
+
+
 @dataclass
 class Level:
     grid: Tuple[int, int, int]
@@ -99,11 +114,15 @@ class BranchRunner:
                 lvl += 1
             self.acts.append(torch.empty((self.levels[lvl].cap, layer.cout), dtype=_TD[dtype], device=device))
 
-    def run(self, points: torch.Tensor, batch: Optional[torch.Tensor]) -> torch.Tensor:
+    def run(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> torch.Tensor:
+        """One pass of the branch.  `timer`, if given, is called as timer(tag) and must return a context
+        manager; it brackets each library call (used by the bench to time kernels with stream events)."""
         ctx, br = self.ctx, self.branch
+        tm = timer if timer is not None else _no_timer
         l0 = self.levels[0]
-        ctx.voxelize(points, batch, br.spec, l0.cap, l0.coords, self.feats32, self.counts, l0.n,
-                     feats_lp=self.feats_lp, index_slot=l0.slot)
+        with tm("voxelize"):
+            ctx.voxelize(points, batch, br.spec, l0.cap, l0.coords, self.feats32, self.counts, l0.n,
+                         feats_lp=self.feats_lp, index_slot=l0.slot)
         x = self.feats32 if self.dtype == F32 else self.feats_lp
         lvl = 0
         built = [False] * len(self.levels)
@@ -113,22 +132,34 @@ class BranchRunner:
             has_epi = layer.epilogue != EPI_NONE
             if layer.kind == STRIDED:
                 src, dst = self.levels[lvl], self.levels[lvl + 1]
-                ctx.build_kmap(B.STRIDED, src.coords, src.n, src.cap, src.grid, nb, dst.cap, dst.down_nbr, dst.n,
-                               out_coords=dst.coords, in_slot=src.slot, out_slot=dst.slot)
+                with tm("kmap_strided"):
+                    ctx.build_kmap(B.STRIDED, src.coords, src.n, src.cap, src.grid, nb, dst.cap, dst.down_nbr, dst.n,
+                                   out_coords=dst.coords, in_slot=src.slot, out_slot=dst.slot)
                 lvl += 1
                 nbr, lv = dst.down_nbr, dst
             else:
                 lv = self.levels[lvl]
                 if not built[lvl]:
-                    ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n,
-                                   in_slot=lv.slot)
+                    with tm("kmap_subm"):
+                        ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n,
+                                       in_slot=lv.slot)
                     built[lvl] = True
                 nbr = lv.subm_nbr
             y = self.acts[li]
-            ctx.spconv(self.dtype, x, p["w"], p["scale"] if has_epi else None, p["shift"] if has_epi else None,
-                       layer.epilogue, nbr, lv.n, lv.cap, y)
+            with tm(("conv", li)):
+                ctx.spconv(self.dtype, x, p["w"], p["scale"] if has_epi else None, p["shift"] if has_epi else None,
+                           layer.epilogue, nbr, lv.n, lv.cap, y)
             x = y
         return x
+
+    def layer_map(self, li: int) -> Tuple[torch.Tensor, "Level"]:
+        """Kernel map and output level used by layer `li` (valid after a run)."""
+        lvl = 0
+        for j, layer in enumerate(self.branch.layers[: li + 1]):
+            if layer.kind == STRIDED:
+                lvl += 1
+        lv = self.levels[lvl]
+        return (lv.down_nbr if self.branch.layers[li].kind == STRIDED else lv.subm_nbr), lv
 
 
 def make_context_for(cfg: Config, capacities: Optional[Dict[str, Sequence[int]]] = None) -> Tuple[B.Context, int]:
