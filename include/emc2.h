@@ -129,19 +129,41 @@ emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d
 
 typedef enum { EMC2_EPI_NONE = 0, EMC2_EPI_AFFINE = 1, EMC2_EPI_AFFINE_RELU = 2 } emc2_epilogue;
 
+/* Weight layouts accepted by emc2_spconv: plain [27][Cin][Cout], or the matrix-core fragment order
+ * produced by emc2_pack_weights (same byte size; only for channel counts the MFMA kernels cover). */
+typedef enum { EMC2_W_PLAIN = 0, EMC2_W_PACKED = 1 } emc2_wlayout;
+
+/*
+ * 1 if (dtype, Cin, Cout) runs on the MFMA kernels (and therefore accepts EMC2_W_PACKED), else 0.
+ * Host-only query, no GPU work.
+ */
+int32_t emc2_spconv_uses_mfma(emc2_dtype dtype, int32_t cin, int32_t cout);
+
+/*
+ * Re-order static weights once (model-load time) into the MFMA fragment order, so that the conv
+ * does not have to do it per call (paper Sec. 3.6: graph-level optimisation of static operands).
+ *   d_w [27][Cin][Cout] and d_packed [27*Cin*Cout], both of `dtype` (F16/BF16); must not overlap.
+ * EMC2_ERR_UNSUPPORTED if emc2_spconv_uses_mfma(dtype, cin, cout) == 0.
+ */
+emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, int32_t cin, int32_t cout,
+                              void* d_packed, void* stream);
+
 /*
  * Sparse convolution over a kernel map, output-stationary gather-GEMM (paper Sec. 3.5: customised
  * 3D sparse convolution, the bulk of inference time; Sec. 3.6: graph fusion -> the folded-BN affine
  * and ReLU are fused into the epilogue):
  *   acc[o][c'] = sum_{k : nbr[k][o] >= 0} sum_c in[nbr[k][o]][c] * w[k][c][c']      (fp32 accumulate)
  *   out[o][c'] = acc | acc*scale[c'] + shift[c'] | max(0, acc*scale[c'] + shift[c'])
- *   d_in  [n_in][Cin], d_w [27][Cin][Cout], d_out [capacity_out][Cout]: all of `dtype`
+ *   d_in  [n_in][Cin], d_out [capacity_out][Cout], d_w: all of `dtype`;
+ *   d_w in `w_layout`: EMC2_W_PLAIN = [27][Cin][Cout] (on the MFMA path it is re-ordered into
+ *   context scratch by one extra small kernel per call), EMC2_W_PACKED = output of emc2_pack_weights
  *   d_scale, d_shift [Cout] fp32 (NULL iff EMC2_EPI_NONE)
  *   d_nbr [27][capacity_out] from emc2_build_kmap; d_n_out device int32 count of outputs.
- * F16/BF16 run on MFMA for Cin, Cout in {16, 32, 64, 128} (Cin = 4 also accepted); other channel
- * counts and F32 run on the vector ALU.  Rows [n_out, capacity_out) of d_out are not written.
+ * F16/BF16 run on MFMA for Cin in {16,32,64,128} and Cout in {32,64,128}; other channel counts
+ * (Cin <= 1024, Cout <= 256) and F32 run on the vector ALU.  Rows [n_out, capacity_out) of d_out
+ * are not written.
  */
-emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
+emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w, emc2_wlayout w_layout,
                         const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
                         const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out,
                         int32_t cin, int32_t cout, void* d_out, void* stream);

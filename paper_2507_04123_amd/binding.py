@@ -21,11 +21,12 @@ OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = 0, 1, 2, 3, 4
 F32, F16, BF16 = 0, 1, 2
 SUBM, STRIDED = 0, 1
 EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
+W_PLAIN, W_PACKED = 0, 1
 
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
-           "emc2_build_kmap", "emc2_spconv", "emc2_project_gather"]
+           "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma"]
 
 
 class Emc2Error(RuntimeError):
@@ -67,7 +68,11 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_build_kmap.argtypes = [vp, ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i32, i32, i64, vp, vp, vp,
                                     ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
     lib.emc2_spconv.restype = ctypes.c_int
-    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, vp, vp, ctypes.c_int, vp, vp, i64, i32, i32, vp, vp]
+    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, i64, i32, i32, vp, vp]
+    lib.emc2_pack_weights.restype = ctypes.c_int
+    lib.emc2_pack_weights.argtypes = [vp, ctypes.c_int, vp, i32, i32, vp, vp]
+    lib.emc2_spconv_uses_mfma.restype = i32
+    lib.emc2_spconv_uses_mfma.argtypes = [ctypes.c_int, i32, i32]
     lib.emc2_project_gather.restype = ctypes.c_int
     lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
     _lib = lib
@@ -171,9 +176,22 @@ class Context:
                                            ctypes.byref(h_n) if sync_count else None, _stream()))
         return (g_out[0], g_out[1], g_out[2]), (int(h_n.value) if sync_count else None)
 
+    def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
+        return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))
+
+    def pack_weights(self, dtype: int, w: torch.Tensor, packed: torch.Tensor) -> None:
+        """w [27][Cin][Cout] -> packed (same shape/dtype buffer) in MFMA fragment order."""
+        td = _TORCH_DTYPE[dtype]
+        _dev_check(w, td, "w")
+        _dev_check(packed, td, "packed")
+        if w.dim() != 3 or w.shape[0] != 27 or packed.numel() != w.numel():
+            raise ValueError("w must be [27][Cin][Cout] and packed the same size")
+        self._chk(self.lib.emc2_pack_weights(self.h, dtype, _ptr(w), int(w.shape[1]), int(w.shape[2]), _ptr(packed),
+                                             _stream()))
+
     def spconv(self, dtype: int, x: torch.Tensor, w: torch.Tensor, scale: Optional[torch.Tensor],
                shift: Optional[torch.Tensor], epilogue: int, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int,
-               out: torch.Tensor) -> None:
+               out: torch.Tensor, w_layout: int = W_PLAIN) -> None:
         td = _TORCH_DTYPE[dtype]
         _dev_check(x, td, "x")
         _dev_check(w, td, "w")
@@ -190,7 +208,7 @@ class Context:
             _dev_check(shift, torch.float32, "shift")
             if scale.numel() != cout or shift.numel() != cout:
                 raise ValueError("scale/shift must have Cout entries")
-        self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
+        self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), w_layout, _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
                                        _ptr(n_out), capacity_out, cin, cout, _ptr(out), _stream()))
 
     def project_gather(self, points: torch.Tensor, pmat: Sequence[float], img: torch.Tensor, out: torch.Tensor,

@@ -58,6 +58,7 @@ struct emc2_ctx {
   uint32_t* partials;       // scan partial sums
   int64_t n_partials;
   int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count
+  void* wpack;              // scratch for weights re-ordered per call (27*128*128 16-bit values)
   int32_t* pinned;          // pinned host staging for counts / status (4 ints)
   char err[256];
 };

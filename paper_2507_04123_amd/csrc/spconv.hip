@@ -54,10 +54,25 @@ void launch_alu(const void* d_in, const void* d_w, const float* d_scale, const f
 
 }  // namespace
 
+extern "C" int32_t emc2_spconv_uses_mfma(emc2_dtype dtype, int32_t cin, int32_t cout) {
+  return (dtype == EMC2_F16 || dtype == EMC2_BF16) && emc2_spconv_mfma_supported(cin, cout) ? 1 : 0;
+}
+
+extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, int32_t cin, int32_t cout,
+                                         void* d_packed, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (!d_w || !d_packed || d_w == d_packed) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_pack_weights: bad pointers");
+  if (!emc2_spconv_uses_mfma(dtype, cin, cout))
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_pack_weights: (dtype, Cin=%d, Cout=%d) does not use the MFMA path", cin,
+                     cout);
+  emc2_spconv_mfma_pack(d_w, cin, cout, d_packed, (hipStream_t)stream);
+  return emc2_check_hip(ctx, hipGetLastError(), "emc2_pack_weights launch");
+}
+
 extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
-                                   const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
-                                   const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t cin,
-                                   int32_t cout, void* d_out, void* stream) {
+                                   emc2_wlayout w_layout, const float* d_scale, const float* d_shift,
+                                   emc2_epilogue epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
+                                   int64_t capacity_out, int32_t cin, int32_t cout, void* d_out, void* stream) {
   if (!ctx) return EMC2_ERR_INVALID_ARG;
   if (!d_in || !d_w || !d_nbr || !d_n_out || !d_out)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: null argument");
@@ -70,10 +85,20 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: channels outside Cin<=1024, Cout<=256");
   if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16)
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: bad dtype");
+  if (w_layout != EMC2_W_PLAIN && w_layout != EMC2_W_PACKED)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: bad weight layout");
+  const bool mfma = emc2_spconv_uses_mfma(dtype, cin, cout) != 0;
+  if (w_layout == EMC2_W_PACKED && !mfma)
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: packed weights need an MFMA-covered (dtype, Cin, Cout)");
   hipStream_t s = (hipStream_t)stream;
-  if (dtype != EMC2_F32 && emc2_spconv_mfma_supported(cin, cout)) {
-    emc2_spconv_mfma_launch(dtype, d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
-                            d_out, s);
+  if (mfma) {
+    const void* wp = d_w;
+    if (w_layout == EMC2_W_PLAIN) {
+      emc2_spconv_mfma_pack(d_w, cin, cout, ctx->wpack, s);  // stream order protects the shared scratch
+      wp = ctx->wpack;
+    }
+    emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out,
+                            s);
   } else if (dtype == EMC2_F32) {
     launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
   } else if (dtype == EMC2_F16) {

@@ -8,6 +8,10 @@
 // true iff (cin, cout) is covered by an MFMA instantiation (16-bit dtypes only)
 bool emc2_spconv_mfma_supported(int cin, int cout);
 
-void emc2_spconv_mfma_launch(emc2_dtype dtype, const void* d_in, const void* d_w, const float* d_scale,
+// Re-order W[27][Cin][Cout] (16-bit) into MFMA B-fragment order (same byte size).
+void emc2_spconv_mfma_pack(const void* d_w, int cin, int cout, void* d_packed, hipStream_t stream);
+
+// d_wp: weights already in fragment order.
+void emc2_spconv_mfma_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                              const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
                              int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream);

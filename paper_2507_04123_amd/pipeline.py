@@ -81,6 +81,15 @@ class BranchRunner:
                  capacities: Optional[Sequence[int]] = None, slot_base: int = 0, device: str = "cuda"):
         self.ctx, self.branch, self.dtype = ctx, branch, dtype
         self.params = params
+        # static weights: re-order once for the MFMA path (model-load time, not part of a frame)
+        self.wdev: List[Tuple[torch.Tensor, int]] = []
+        for layer, p in zip(branch.layers, params):
+            if ctx.uses_mfma(dtype, layer.cin, layer.cout):
+                packed = torch.empty_like(p["w"])
+                ctx.pack_weights(dtype, p["w"], packed)
+                self.wdev.append((packed, B.W_PACKED))
+            else:
+                self.wdev.append((p["w"], B.W_PLAIN))
         caps = list(capacities) if capacities is not None else default_capacities(branch, n_points)
         self.levels: List[Level] = []
         grid = tuple(branch.spec.grid)
@@ -147,8 +156,9 @@ class BranchRunner:
                 nbr = lv.subm_nbr
             y = self.acts[li]
             with tm(("conv", li)):
-                ctx.spconv(self.dtype, x, p["w"], p["scale"] if has_epi else None, p["shift"] if has_epi else None,
-                           layer.epilogue, nbr, lv.n, lv.cap, y)
+                ctx.spconv(self.dtype, x, self.wdev[li][0], p["scale"] if has_epi else None,
+                           p["shift"] if has_epi else None, layer.epilogue, nbr, lv.n, lv.cap, y,
+                           w_layout=self.wdev[li][1])
             x = y
         return x
 

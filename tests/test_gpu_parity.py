@@ -236,7 +236,7 @@ def test_kmap_configs_full_size(cfg_index):
 # sparse conv
 # ------------------------------------------------------------------------------------------------
 
-def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None):
+def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None, packed=False):
     n_out = nbr_np.shape[1]
     cap = cap or max(n_out, 1)
     nbr = torch.full((27, cap), -1, dtype=torch.int32, device="cuda")
@@ -245,8 +245,13 @@ def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None):
     w = dev(w_np, TD[dtype])
     out = torch.full((cap, w_np.shape[2]), 768.0, dtype=TD[dtype], device="cuda")
     n_t = torch.tensor([n_out], dtype=torch.int32, device="cuda")
+    layout = B.W_PLAIN
+    if packed:
+        wp = torch.empty_like(w)
+        ctx.pack_weights(dtype, w, wp)
+        w, layout = wp, B.W_PACKED
     ctx.spconv(dtype, x, w, None if scale is None else dev(scale), None if shift is None else dev(shift), epi, nbr, n_t,
-               cap, out)
+               cap, out, w_layout=layout)
     torch.cuda.synchronize()
     return out
 
@@ -285,9 +290,14 @@ def test_spconv_subm_and_strided_small(dtype, cin, cout, grid, n, epi):
         print(f"spconv dtype={dtype} {cin}->{cout} kind={kind} n_out={nbr.shape[1]} epi={epi}", flush=True)
         exp = oracle.spconv(x, w, scale, shift, epi, nbr)
         cap = nbr.shape[1] + 37                                  # capacity beyond n_out: tail must stay untouched
-        got = gpu_spconv(ctx, dtype, x, w, scale, shift, epi, nbr, cap=cap)
-        assert_features_close(got[:nbr.shape[1]].float().cpu().numpy(), exp, RTOL[dtype], f"spconv {cin}->{cout}")
-        assert torch.all(got[nbr.shape[1]:].float() == 768.0)
+        layouts = [False, True] if ctx.uses_mfma(dtype, cin, cout) else [False]
+        for packed in layouts:
+            got = gpu_spconv(ctx, dtype, x, w, scale, shift, epi, nbr, cap=cap, packed=packed)
+            assert_features_close(got[:nbr.shape[1]].float().cpu().numpy(), exp, RTOL[dtype], f"spconv {cin}->{cout}")
+            assert torch.all(got[nbr.shape[1]:].float() == 768.0)
+    if not ctx.uses_mfma(dtype, cin, cout) and dtype != F32:
+        with pytest.raises(B.Emc2Error):                         # packed layout only exists for MFMA shapes
+            ctx.pack_weights(dtype, dev(w, TD[dtype]), torch.empty_like(dev(w, TD[dtype])))
     ctx.close()
 
 
