@@ -86,10 +86,12 @@ template <int CIN, int COUT> struct Pipe {
   static constexpr int D = CIN <= 64 ? 3 : 1;                     // 1 or 3
   static constexpr int WD = (CIN * COUT <= 64 * 64) ? 3 : 1;      // 1 or 3
   static constexpr int NB = WD == 3 ? 3 : 2;                      // weight buffers in LDS
+  // waves per SIMD the register allocator must leave room for (2 where LDS also lets two blocks share a CU)
+  static constexpr int MINW = (CIN <= 64 && COUT <= 64) ? 2 : 1;
 };
 
 template <int DT, int CIN, int COUT, int MT>
-__global__ void __launch_bounds__(kThreads) k_spconv_mfma(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp,
+__global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mfma(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp,
                                                           const float* __restrict__ scale, const float* __restrict__ shift,
                                                           int epilogue, const int32_t* __restrict__ nbr,
                                                           const int32_t* __restrict__ d_n_out, int64_t capacity_out,
