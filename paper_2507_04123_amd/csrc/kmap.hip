@@ -2,36 +2,70 @@
 // voxels are computed; Sec. 3.6: prefix-sum index search).
 //
 // SUBM   : for every active voxel o and tap k, look up cell(o) - 1 + k in the input cell index.
-// STRIDED: each input marks the (at most 8) outputs whose 3x3x3 window contains it in the output
-//          cell index; the scan ranks them (= ascending key order); the set bits are expanded to
-//          coordinates; then every output probes the input index at 2*o - 1 + k.
+// STRIDED: every 32-cell word of the input cell index marks, with bit arithmetic, the outputs whose
+//          3x3x3 window contains one of its voxels in the output cell index; the scan ranks them
+//          (= ascending key order); the set bits are expanded to coordinates; then every output
+//          probes the input index at 2*o - 1 + k.
 #include "common.h"
 
 namespace {
 
-__global__ void __launch_bounds__(256) k_strided_mark(const int4* __restrict__ in_coords, const int32_t* __restrict__ d_n_in,
-                                                      int64_t capacity_in, cellword_t* __restrict__ out_idx, int gox,
-                                                      int goy, int goz, int gx, int gy, int gz, int n_batch) {
-  int64_t n = *d_n_in;
-  if (n > capacity_in) n = capacity_in;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const int4 c = in_coords[i];  // (b, z, y, x)
-  if ((unsigned)c.x >= (unsigned)n_batch || (unsigned)c.y >= (unsigned)gz || (unsigned)c.z >= (unsigned)gy ||
-      (unsigned)c.w >= (unsigned)gx)
-    return;  // malformed coordinate: ignore rather than write out of bounds
-  // input coordinate v is read by outputs o with 2o-1 <= v <= 2o+1: o = v/2 if v even, (v-1)/2 and (v+1)/2 if odd
-  const int x0 = c.w >> 1, nx = ((c.w & 1) && (x0 + 1 < gox)) ? 2 : 1;
-  const int y0 = c.z >> 1, ny = ((c.z & 1) && (y0 + 1 < goy)) ? 2 : 1;
-  const int z0 = c.y >> 1, nz = ((c.y & 1) && (z0 + 1 < goz)) ? 2 : 1;
-  for (int dz = 0; dz < nz; ++dz)
-    for (int dy = 0; dy < ny; ++dy) {
-      const uint64_t row = (((uint64_t)c.x * goz + (uint64_t)(z0 + dz)) * goy + (uint64_t)(y0 + dy)) * gox;
-      for (int dx = 0; dx < nx; ++dx) {
-        const uint64_t key = row + (uint64_t)(x0 + dx);
-        atomicOr(&out_idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+// Keep the even-numbered bits of v (bit 2i -> bit i).
+__device__ __forceinline__ uint32_t compress_even_bits(uint64_t v) {
+  v &= 0x5555555555555555ull;
+  v = (v | (v >> 1)) & 0x3333333333333333ull;
+  v = (v | (v >> 2)) & 0x0f0f0f0f0f0f0f0full;
+  v = (v | (v >> 4)) & 0x00ff00ff00ff00ffull;
+  v = (v | (v >> 8)) & 0x0000ffff0000ffffull;
+  v = (v | (v >> 16)) & 0x00000000ffffffffull;
+  return (uint32_t)v;
+}
+
+// Stride-2 output occupancy, one thread per 32-cell word of the INPUT cell index.  An input at x is read
+// by outputs o with 2o-1 <= x <= 2o+1, so with the word's bits S laid out at their absolute x parity,
+// output bit i is S[2i-1] | S[2i] | S[2i+1]: a shift-or and an even-bit compress give up to 18 output
+// bits at once, which are OR-ed into at most two output words per (z, y) parity combination.  Working on
+// words instead of voxels turns hundreds of colliding single-bit atomics per output word into a few.
+__global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restrict__ in_idx, int64_t n_in_words,
+                                                      int64_t n_in_cells, cellword_t* __restrict__ out_idx, int gx, int gy,
+                                                      int gz, int gox, int goy, int goz) {
+  const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w >= n_in_words) return;
+  uint32_t bits = in_idx[w].x;
+  while (bits) {
+    // row segment of the word that starts at the first set bit's row
+    const int first = __ffs((int)bits) - 1;
+    uint64_t key = (uint64_t)w * 32 + (uint64_t)first;
+    if ((int64_t)key >= n_in_cells) return;  // padding bits past the grid are never set; defensive
+    uint64_t k = key;
+    const int x = (int)(k % (uint64_t)gx); k /= (uint64_t)gx;
+    const int y = (int)(k % (uint64_t)gy); k /= (uint64_t)gy;
+    const int z = (int)(k % (uint64_t)gz); k /= (uint64_t)gz;
+    const uint64_t b = k;
+    const int room = gx - x;                       // cells left in this row from the first set bit
+    const int avail = 32 - first;                  // bits left in this word
+    const int len = room < avail ? room : avail;   // segment [first, first + len)
+    const uint32_t seg_mask = (len >= 32 ? 0xffffffffu : ((1u << len) - 1u)) << first;
+    const uint32_t s = (bits & seg_mask) >> first; // bit j <-> input x + j
+    bits &= ~seg_mask;
+    const int p = x & 1;
+    const uint64_t S = (uint64_t)s << (p + 1);     // bit j+1 <-> input x' = (x - p) + j; one spare bit below
+    const uint64_t U = S | (S << 1) | (S >> 1);    // bit 2i+1 <-> S[2i-1+1] | S[2i+1] | S[2i+1+1]
+    uint32_t m = compress_even_bits(U >> 1);       // bit i <-> output x = (x >> 1) + i
+    const int ob = x >> 1;
+    const int left = gox - ob;                     // outputs left in the output row
+    if (left < 32) m &= (1u << left) - 1u;
+    if (!m) continue;
+    const int z0 = z >> 1, nz = ((z & 1) && (z0 + 1 < goz)) ? 2 : 1;
+    const int y0 = y >> 1, ny = ((y & 1) && (y0 + 1 < goy)) ? 2 : 1;
+    for (int dz = 0; dz < nz; ++dz)
+      for (int dy = 0; dy < ny; ++dy) {
+        const uint64_t okey = ((b * goz + (uint64_t)(z0 + dz)) * goy + (uint64_t)(y0 + dy)) * gox + (uint64_t)ob;
+        const uint32_t sh = (uint32_t)okey & 31u;
+        atomicOr(&out_idx[okey >> 5].x, m << sh);
+        if (sh != 0 && (m >> (32u - sh)) != 0) atomicOr(&out_idx[(okey >> 5) + 1].x, m >> (32u - sh));
       }
-    }
+  }
 }
 
 // One thread per cellword: expand set bits into coordinates at their rank.
@@ -162,7 +196,9 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
 
   const int32_t* out_coords = d_in_coords;
   if (kind == EMC2_CONV_SUBM) {
-    hipLaunchKernelGGL(k_copy_count, dim3(1), dim3(1), 0, s, d_n_in, d_n_out, capacity_out, ctx->dev_words);
+    // the count only needs a kernel when it moves or can be clamped
+    if (d_n_out != d_n_in || capacity_out < capacity_in)
+      hipLaunchKernelGGL(k_copy_count, dim3(1), dim3(1), 0, s, d_n_in, d_n_out, capacity_out, ctx->dev_words);
     if (d_out_coords && d_out_coords != d_in_coords) {
       const int64_t m = capacity_in < capacity_out ? capacity_in : capacity_out;
       hipLaunchKernelGGL(k_copy_coords, dim3((unsigned)emc2_div_up(m, 256)), dim3(256), 0, s, (const int4*)d_in_coords,
@@ -180,9 +216,11 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
       m.valid = true;
     }
     emc2_index_clear(ctx, out_idx, cells_out, s);
-    hipLaunchKernelGGL(k_strided_mark, dim3((unsigned)emc2_div_up(capacity_in, 256)), dim3(256), 0, s,
-                       (const int4*)d_in_coords, d_n_in, capacity_in, out_idx, go[0], go[1], go[2], grid_in[0], grid_in[1],
-                       grid_in[2], n_batch);
+    {
+      const int64_t n_in_words = emc2_div_up(cells_in, 32);
+      hipLaunchKernelGGL(k_strided_mark, dim3((unsigned)emc2_div_up(n_in_words, 256)), dim3(256), 0, s, in_idx, n_in_words,
+                         cells_in, out_idx, grid_in[0], grid_in[1], grid_in[2], go[0], go[1], go[2]);
+    }
     emc2_index_scan(ctx, out_idx, cells_out, capacity_out, d_n_out, s);
     const int64_t n_words = emc2_div_up(cells_out, 32);
     hipLaunchKernelGGL(k_expand_coords, dim3((unsigned)emc2_div_up(n_words, 256)), dim3(256), 0, s, out_idx, n_words,
