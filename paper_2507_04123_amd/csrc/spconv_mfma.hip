@@ -88,6 +88,9 @@ template <int CIN, int COUT> struct Pipe {
   static constexpr int NB = WD == 3 ? 3 : 2;                      // weight buffers in LDS
   // waves per SIMD the register allocator must leave room for (2 where LDS also lets two blocks share a CU)
   static constexpr int MINW = (CIN <= 64 && COUT <= 64) ? 2 : 1;
+  // skip the LDS and matrix work of a tap at which none of the wave's 64 rows has a neighbour: measured to
+  // pay only where a tap is expensive (Cin = 64) and the accumulators live in ordinary VGPRs (MINW = 2)
+  static constexpr bool SKIP = (CIN == 64 && COUT <= 64);
 };
 
 template <int DT, int CIN, int COUT, int MT>
@@ -118,8 +121,15 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
 
   int64_t n_out = *d_n_out;
   if (n_out > capacity_out) n_out = capacity_out;
-  const int64_t block_row0 = (int64_t)blockIdx.x * (kWaves * R);
-  if (block_row0 >= n_out) return;  // whole block past the end (uniform)
+  // XCD-aware tile assignment: workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
+  // workgroup b runs on XCD b % 8.  Giving XCD x the contiguous tile range [x*chunk, (x+1)*chunk) keeps
+  // spatially adjacent tiles -- which gather largely the same input rows -- behind one L2.
+  const int64_t n_tiles = (n_out + kWaves * R - 1) / (kWaves * R);
+  const int64_t chunk = (n_tiles + 7) / 8;
+  const int64_t slot_in_xcd = blockIdx.x / 8;
+  const int64_t tile_id = (int64_t)(blockIdx.x % 8) * chunk + slot_in_xcd;
+  if (slot_in_xcd >= chunk || tile_id >= n_tiles) return;  // uniform for the block
+  const int64_t block_row0 = tile_id * (kWaves * R);
 
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
@@ -203,8 +213,12 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
       // weights of tap + WD: global -> registers (the set was emptied at the end of the previous tap)
       EMC2_W_LOAD(tap + WD < 27 ? tap + WD : 26, kx % WD)
       // gathered rows of this tap: registers -> wave-private LDS tile
+      // a tap at which none of the wave's 64 rows has a neighbour does no LDS or matrix work at all; the
+      // loads stay unconditional (see above), only their use is skipped (wave-uniform branch)
+      if (!Pipe<CIN, COUT>::SKIP || mask != 0ull) {
 #pragma unroll
-      for (int i = 0; i < NI; ++i) my_tile[(i * RPI + srow) * ROW16 + schunk] = sreg[kx % D][i];
+        for (int i = 0; i < NI; ++i) my_tile[(i * RPI + srow) * ROW16 + schunk] = sreg[kx % D][i];
+      }
       // the freed register set takes the gather of tap + D (absent entries re-read row 0 and are masked)
       const int32_t past = g < 8 ? 0 : -1;   // entries of "group 9" do not exist
       if constexpr (D == 3) {
@@ -214,10 +228,9 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
       }
       __builtin_amdgcn_wave_barrier();
       const u32x4* wb = wl[tap % NB];
-      {
-        // branch-free on purpose: a branch around the MFMAs makes the accumulators live across control
-        // flow and the compiler then copies all of them between AGPRs and VGPRs on every tap, which
-        // costs far more issue slots than the skipped matrix work would save
+      if (!Pipe<CIN, COUT>::SKIP || mask != 0ull) {
+        // no per-tile branches inside: with finer-grained conditions around the MFMAs the compiler starts
+        // copying accumulators between register classes on every tap
         const bool v0 = (mask >> m) & 1ull, v1 = (mask >> (32 + m)) & 1ull;
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
@@ -281,7 +294,8 @@ void launch(const void* d_in, const void* d_wp, const float* d_scale, const floa
             const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, void* d_out, hipStream_t s) {
   constexpr int MT = 2;
   const int64_t rows_per_block = kWaves * MT * 32;
-  hipLaunchKernelGGL((k_spconv_mfma<DT, CIN, COUT, MT>), dim3((unsigned)emc2_div_up(capacity_out, rows_per_block)),
+  hipLaunchKernelGGL((k_spconv_mfma<DT, CIN, COUT, MT>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),  // + 8: the per-XCD ranges round up
+                    
                      dim3(kThreads), 0, s, (const uint16_t*)d_in, (const u32x4*)d_wp, d_scale, d_shift, epilogue, d_nbr,
                      d_n_out, capacity_out, (uint16_t*)d_out);
 }
