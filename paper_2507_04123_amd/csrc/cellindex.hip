@@ -109,6 +109,83 @@ __global__ void __launch_bounds__(256) k_scan_apply(cellword_t* __restrict__ idx
   }
 }
 
+// Whole scan in one block (small grids: the coarse levels): thread t owns a contiguous run of words.
+__global__ void __launch_bounds__(1024) k_scan_small(cellword_t* __restrict__ idx, int64_t n_words, int64_t capacity,
+                                                     int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags) {
+  const int per = (int)((n_words + 1023) / 1024);
+  const int64_t base = (int64_t)threadIdx.x * per;
+  uint32_t s = 0;
+  for (int j = 0; j < per; ++j)
+    if (base + j < n_words) s += __popc(idx[base + j].x);
+  __shared__ uint32_t wsum[16];
+  const uint32_t inc = wave_inclusive_scan(s);
+  if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+  __syncthreads();
+  uint32_t run = inc - s;
+  const int w = threadIdx.x >> 6;
+  for (int j = 0; j < w; ++j) run += wsum[j];
+  for (int j = 0; j < per; ++j)
+    if (base + j < n_words) {
+      const uint32_t bits = idx[base + j].x;
+      idx[base + j] = make_uint2(bits, run);
+      run += __popc(bits);
+    }
+  if (threadIdx.x == 1023) {
+    if ((int64_t)run > capacity) {
+      atomicOr(d_flags, EMC2_DEVFLAG_CAPACITY);
+      *d_total = (int32_t)capacity;
+    } else {
+      *d_total = (int32_t)run;
+    }
+  }
+}
+
+// Apply step that derives its own base from the block totals (no separate scan of the totals): block b
+// sums totals[0..b) cooperatively.  Quadratic in the number of blocks, so only used while that is small.
+__global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict__ idx, int64_t n_words,
+                                                         const uint32_t* __restrict__ totals, int64_t capacity,
+                                                         int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t base_s;
+  uint32_t part = 0;
+  for (int i = threadIdx.x; i < (int)blockIdx.x; i += 256) part += totals[i];
+  {
+    const uint32_t inc = wave_inclusive_scan(part);
+    if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) base_s = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    __syncthreads();
+  }
+  const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
+  uint32_t bits[8];
+  uint32_t s = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    bits[j] = (base + j < n_words) ? idx[base + j].x : 0u;
+    s += __popc(bits[j]);
+  }
+  const uint32_t inc = wave_inclusive_scan(s);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
+  __syncthreads();
+  uint32_t run = base_s + inc - s;
+  const int w = threadIdx.x >> 6;
+  for (int j = 0; j < w; ++j) run += wsum[j];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
+    run += __popc(bits[j]);
+  }
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {
+    if ((int64_t)run > capacity) {
+      atomicOr(d_flags, EMC2_DEVFLAG_CAPACITY);
+      *d_total = (int32_t)capacity;
+    } else {
+      *d_total = (int32_t)run;
+    }
+  }
+}
+
 }  // namespace
 
 void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, hipStream_t stream) {
@@ -133,7 +210,17 @@ void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t ca
                      hipStream_t stream) {
   const int64_t n_words = emc2_div_up(n_cells, 32);
   const int64_t n_blocks = emc2_div_up(n_words, EMC2_SCAN_TILE);
+  if (n_words <= 64 * 1024) {
+    // coarse levels: one block does it all (one launch instead of three)
+    hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, stream, idx, n_words, capacity, d_total, ctx->dev_words);
+    return;
+  }
   hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);
+  if (n_blocks <= 2048) {
+    hipLaunchKernelGGL(k_scan_apply_self, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
+                       capacity, d_total, ctx->dev_words);
+    return;
+  }
   hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, stream, ctx->partials, n_blocks, capacity, d_total,
                      ctx->dev_words);
   hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);

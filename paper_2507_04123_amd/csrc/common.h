@@ -23,6 +23,23 @@ __device__ __forceinline__ int32_t cell_lookup(const cellword_t* __restrict__ id
   return (int32_t)(w.y + __popc(w.x & ((1u << bit) - 1u)));
 }
 
+// Linear key -> (b, z, y, x).  Keys below 2^32 (every single-frame grid here) take 32-bit divisions, which are
+// several times cheaper than the 64-bit ones.
+__device__ __forceinline__ int4 decode_key(uint64_t key, int gx, int gy, int gz) {
+  if ((key >> 32) == 0) {
+    uint32_t k = (uint32_t)key;
+    const uint32_t x = k % (uint32_t)gx; k /= (uint32_t)gx;
+    const uint32_t y = k % (uint32_t)gy; k /= (uint32_t)gy;
+    const uint32_t z = k % (uint32_t)gz; k /= (uint32_t)gz;
+    return make_int4((int)k, (int)z, (int)y, (int)x);
+  }
+  uint64_t k = key;
+  const int x = (int)(k % (uint64_t)gx); k /= (uint64_t)gx;
+  const int y = (int)(k % (uint64_t)gy); k /= (uint64_t)gy;
+  const int z = (int)(k % (uint64_t)gz); k /= (uint64_t)gz;
+  return make_int4((int)k, z, y, x);
+}
+
 // Voxel hash record (open addressing, linear probing): the key and its running sums share one
 // 32-byte sector so that a point touches a single sector for the CAS and its five atomic adds.
 struct __attribute__((aligned(32))) VoxRec {

@@ -43,10 +43,96 @@ __global__ void __launch_bounds__(256) k_spconv_alu(const T* __restrict__ in, co
   from_f32(out + o * cout + d, acc);
 }
 
+// Small-channel kernel (Cin in {4, 16}, Cout in {16, 32}: the input layers that sit below the matrix-core
+// tile sizes).  One thread owns one output row and all of its Cout accumulators; the 27 taps run in
+// lockstep across the wave, so a tap's weights are LDS broadcasts and a tap nobody in the wave has is
+// skipped.  Kernel-map entries are fetched one tap ahead with an unconditional load.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+
+template <typename T, int CIN, int COUT>
+__global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, const T* __restrict__ w,
+                                                      const float* __restrict__ scale, const float* __restrict__ shift,
+                                                      int epilogue, const int32_t* __restrict__ nbr,
+                                                      const int32_t* __restrict__ d_n_out, int64_t capacity_out,
+                                                      T* __restrict__ out) {
+  __shared__ float wl[27 * CIN * COUT];
+  for (int i = threadIdx.x; i < 27 * CIN * COUT; i += 256) wl[i] = to_f32(w[i]);
+  __syncthreads();
+  int64_t n = *d_n_out;
+  if (n > capacity_out) n = capacity_out;
+  const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const bool live = o < n;
+  const int32_t* nrow = nbr + (live ? o : 0);
+  const int32_t dead = live ? 0 : -1;
+  float acc[COUT];
+#pragma unroll
+  for (int d = 0; d < COUT; ++d) acc[d] = 0.f;
+  constexpr int ROW_BYTES = CIN * (int)sizeof(T);
+  static_assert(ROW_BYTES % 8 == 0, "feature rows are read with 8- or 16-byte loads");
+  int32_t jn = nrow[0];
+  for (int k = 0; k < 27; ++k) {
+    const int32_t j = jn | dead;
+    jn = nrow[(int64_t)(k + 1 < 27 ? k + 1 : 26) * capacity_out];
+    if (__ballot(j >= 0) == 0ull) continue;  // wave-uniform
+    if (j >= 0) {
+      alignas(16) T xr[CIN];
+      const char* src = reinterpret_cast<const char*>(in + (int64_t)j * CIN);
+      if constexpr (ROW_BYTES % 16 == 0) {
+#pragma unroll
+        for (int q = 0; q < ROW_BYTES / 16; ++q)
+          reinterpret_cast<u32x4_t*>(xr)[q] = reinterpret_cast<const u32x4_t*>(src)[q];
+      } else {
+#pragma unroll
+        for (int q = 0; q < ROW_BYTES / 8; ++q)
+          reinterpret_cast<u32x2_t*>(xr)[q] = reinterpret_cast<const u32x2_t*>(src)[q];
+      }
+      const float* wk = wl + k * CIN * COUT;
+#pragma unroll
+      for (int c = 0; c < CIN; ++c) {
+        const float xv = to_f32(xr[c]);
+#pragma unroll
+        for (int d = 0; d < COUT; ++d) acc[d] = fmaf(xv, wk[c * COUT + d], acc[d]);
+      }
+    }
+  }
+  if (!live) return;
+  alignas(16) T yr[COUT];
+#pragma unroll
+  for (int d = 0; d < COUT; ++d) {
+    float v = acc[d];
+    if (epilogue != EMC2_EPI_NONE) v = fmaf(v, scale[d], shift[d]);
+    if (epilogue == EMC2_EPI_AFFINE_RELU) v = v > 0.f ? v : 0.f;
+    from_f32(&yr[d], v);
+  }
+  constexpr int OUT_BYTES = COUT * (int)sizeof(T);
+  static_assert(OUT_BYTES % 16 == 0, "output rows are written with 16-byte stores");
+  char* dst = reinterpret_cast<char*>(out + o * COUT);
+#pragma unroll
+  for (int q = 0; q < OUT_BYTES / 16; ++q) reinterpret_cast<u32x4_t*>(dst)[q] = reinterpret_cast<const u32x4_t*>(yr)[q];
+}
+
+template <typename T>
+bool launch_small(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
+                  const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
+                  hipStream_t s) {
+#define EMC2_SMALL(CI, CO)                                                                                            \
+  if (cin == CI && cout == CO) {                                                                                      \
+    hipLaunchKernelGGL((k_spconv_small<T, CI, CO>), dim3((unsigned)emc2_div_up(capacity_out, 256)), dim3(256), 0, s,  \
+                       (const T*)d_in, (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out,       \
+                       (T*)d_out);                                                                                    \
+    return true;                                                                                                      \
+  }
+  EMC2_SMALL(4, 16) EMC2_SMALL(4, 32) EMC2_SMALL(16, 16)
+#undef EMC2_SMALL
+  return false;
+}
+
 template <typename T>
 void launch_alu(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
                 const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
                 hipStream_t s) {
+  if (launch_small<T>(d_in, d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s)) return;
   const int rows = 256 / cout;
   hipLaunchKernelGGL(k_spconv_alu<T>, dim3((unsigned)emc2_div_up(capacity_out, rows)), dim3(256), 0, s, (const T*)d_in,
                      (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, rows, (T*)d_out);

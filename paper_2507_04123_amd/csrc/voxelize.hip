@@ -131,11 +131,7 @@ __global__ void __launch_bounds__(256) k_vox_finalize(const VoxRec* __restrict__
   const VoxRec rec = table[uslot[id]];
   const int32_t r = cell_lookup(idx, rec.key);
   if (r < 0 || r >= capacity) return;
-  uint64_t k = rec.key;
-  const int x = (int)(k % (uint64_t)gx); k /= (uint64_t)gx;
-  const int y = (int)(k % (uint64_t)gy); k /= (uint64_t)gy;
-  const int z = (int)(k % (uint64_t)gz); k /= (uint64_t)gz;
-  coords[r] = make_int4((int)k, z, y, x);
+  coords[r] = decode_key(rec.key, gx, gy, gz);
   const float c = (float)rec.count;
   const float4 m = make_float4(rec.sum[0] / c, rec.sum[1] / c, rec.sum[2] / c, rec.sum[3] / c);
   feats[r] = m;
