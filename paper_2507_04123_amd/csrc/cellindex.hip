@@ -210,7 +210,7 @@ void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t ca
                      hipStream_t stream) {
   const int64_t n_words = emc2_div_up(n_cells, 32);
   const int64_t n_blocks = emc2_div_up(n_words, EMC2_SCAN_TILE);
-  if (n_words <= 64 * 1024) {
+  if (n_words <= 8 * 1024) {
     // coarse levels: one block does it all (one launch instead of three)
     hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, stream, idx, n_words, capacity, d_total, ctx->dev_words);
     return;
