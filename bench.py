@@ -95,6 +95,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tight-capacity", action="store_true",
                     help="size per-level capacities from a calibration pass (x1.25) instead of the safe bounds")
+    ap.add_argument("--copy-probe-mib", type=int, default=0,
+                    help="also launch one plain device copy of this many MiB (a known-size reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (frames shard across GPUs with no "
@@ -145,6 +148,13 @@ def main() -> int:
         pairs = int((nbr[:, :n] >= 0).sum().item())
         layer_pairs.append(pairs)
         layer_flops.append(2.0 * pairs * layer.cin * layer.cout)
+
+    if args.copy_probe_mib > 0:
+        src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     timer = EventTimer(torch)
     for _ in range(args.warmup):

@@ -117,7 +117,9 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
   constexpr int WD = Pipe<CIN, COUT>::WD;
   constexpr int NB = Pipe<CIN, COUT>::NB;
   __shared__ u32x4 wl[NB][W16];
-  __shared__ u32x4 tile[kWaves][R * ROW16];   // wave-private staging tiles of gathered rows
+  // wave-private tiles: gathered rows of a tap; at the end, 32 output rows at a time on their way to memory
+  constexpr int TILE16 = (R * ROW16 > 32 * (COUT / 8 + 1)) ? R * ROW16 : 32 * (COUT / 8 + 1);
+  __shared__ u32x4 tile[kWaves][TILE16];
 
   int64_t n_out = *d_n_out;
   if (n_out > capacity_out) n_out = capacity_out;
@@ -267,25 +269,42 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
 #undef EMC2_W_LOAD
 #undef EMC2_W_STORE
 
-  // epilogue: lane holds column n = 32*j + m; acc element e <-> row 8*(e/4) + 4*h + (e%4)
+  // epilogue: lane holds column n = 32*j + m; acc element e <-> row 8*(e/4) + 4*h + (e%4).
+  // Scale/shift/ReLU/convert in registers, then each 32-row tile goes through the wave's LDS tile so that
+  // the global stores are whole 16-byte pieces of consecutive rows (a lane-per-column store would write 2
+  // bytes per lane and take as long as several taps).
+  float sc[NT], sh[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    const int n = 32 * j + m;
-    const float sc = (epilogue != EMC2_EPI_NONE) ? scale[n] : 1.f;
-    const float sh = (epilogue != EMC2_EPI_NONE) ? shift[n] : 0.f;
+    sc[j] = (epilogue != EMC2_EPI_NONE) ? scale[32 * j + m] : 1.f;
+    sh[j] = (epilogue != EMC2_EPI_NONE) ? shift[32 * j + m] : 0.f;
+  }
+  uint16_t* otile = reinterpret_cast<uint16_t*>(my_tile);
+  constexpr int OCH = COUT / 8;               // 16-byte pieces per output row
+  constexpr int OPITCH = (OCH + 1) * 8;       // LDS row pitch in 16-bit units (one piece of padding)
+  constexpr int ORPI = 64 / OCH;              // rows one store instruction covers
+  const int orow = lane / OCH, ochunk = lane % OCH;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
+  for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int64_t o = wave_row0 + mt * 32 + 8 * (e / 4) + 4 * h + (e % 4);
-        if (o < n_out) {
-          float v = acc[mt][j][e];
-          if (epilogue != EMC2_EPI_NONE) v = fmaf(v, sc, sh);
-          if (epilogue == EMC2_EPI_AFFINE_RELU) v = v > 0.f ? v : 0.f;
-          out[o * COUT + n] = Mma<DT>::cvt(v);
-        }
+        float v = acc[mt][j][e];
+        if (epilogue != EMC2_EPI_NONE) v = fmaf(v, sc[j], sh[j]);
+        if (epilogue == EMC2_EPI_AFFINE_RELU) v = v > 0.f ? v : 0.f;
+        otile[(8 * (e / 4) + 4 * h + (e % 4)) * OPITCH + 32 * j + m] = Mma<DT>::cvt(v);
       }
     }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 32 / ORPI; ++i) {
+      const int r = i * ORPI + orow;
+      const u32x4 piece = *reinterpret_cast<const u32x4*>(otile + r * OPITCH + ochunk * 8);
+      const int64_t o = wave_row0 + mt * 32 + r;
+      if (o < n_out) *reinterpret_cast<u32x4*>(out + o * COUT + ochunk * 8) = piece;
+    }
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
