@@ -162,10 +162,14 @@ emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, 
  * F16/BF16 run on MFMA for Cin in {16,32,64,128} and Cout in {32,64,128}; other channel counts
  * (Cin <= 1024, Cout <= 256) and F32 run on the vector ALU.  Rows [n_out, capacity_out) of d_out
  * are not written.
+ *   map_hint: EMC2_CONV_SUBM / EMC2_CONV_STRIDED if d_nbr came from emc2_build_kmap with that kind, else
+ *   EMC2_MAP_ANY.  A scheduling hint only (submanifold maps over key-sorted voxels let the three kx
+ *   taps of a (dz, dy) pair share one fetch of input rows): results do not depend on it, for any table.
  */
+#define EMC2_MAP_ANY (-1)
 emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w, emc2_wlayout w_layout,
                         const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
-                        const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out,
+                        const int32_t* d_nbr, int32_t map_hint, const int32_t* d_n_out, int64_t capacity_out,
                         int32_t cin, int32_t cout, void* d_out, void* stream);
 
 /*

@@ -22,6 +22,7 @@ F32, F16, BF16 = 0, 1, 2
 SUBM, STRIDED = 0, 1
 EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
 W_PLAIN, W_PACKED = 0, 1
+MAP_ANY = -1   # emc2_spconv map_hint: SUBM / STRIDED as passed to build_kmap, or unknown
 
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
@@ -68,7 +69,7 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_build_kmap.argtypes = [vp, ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i32, i32, i64, vp, vp, vp,
                                     ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
     lib.emc2_spconv.restype = ctypes.c_int
-    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, i64, i32, i32, vp, vp]
+    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, i32, vp, i64, i32, i32, vp, vp]
     lib.emc2_pack_weights.restype = ctypes.c_int
     lib.emc2_pack_weights.argtypes = [vp, ctypes.c_int, vp, i32, i32, vp, vp]
     lib.emc2_spconv_uses_mfma.restype = i32
@@ -191,7 +192,7 @@ class Context:
 
     def spconv(self, dtype: int, x: torch.Tensor, w: torch.Tensor, scale: Optional[torch.Tensor],
                shift: Optional[torch.Tensor], epilogue: int, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int,
-               out: torch.Tensor, w_layout: int = W_PLAIN) -> None:
+               out: torch.Tensor, w_layout: int = W_PLAIN, map_hint: int = MAP_ANY) -> None:
         td = _TORCH_DTYPE[dtype]
         _dev_check(x, td, "x")
         _dev_check(w, td, "w")
@@ -209,7 +210,7 @@ class Context:
             if scale.numel() != cout or shift.numel() != cout:
                 raise ValueError("scale/shift must have Cout entries")
         self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), w_layout, _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
-                                       _ptr(n_out), capacity_out, cin, cout, _ptr(out), _stream()))
+                                       map_hint, _ptr(n_out), capacity_out, cin, cout, _ptr(out), _stream()))
 
     def project_gather(self, points: torch.Tensor, pmat: Sequence[float], img: torch.Tensor, out: torch.Tensor,
                        valid: torch.Tensor, uv: Optional[torch.Tensor] = None) -> None:

@@ -157,8 +157,9 @@ extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const 
 
 extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
                                    emc2_wlayout w_layout, const float* d_scale, const float* d_shift,
-                                   emc2_epilogue epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
-                                   int64_t capacity_out, int32_t cin, int32_t cout, void* d_out, void* stream) {
+                                   emc2_epilogue epilogue, const int32_t* d_nbr, int32_t map_hint,
+                                   const int32_t* d_n_out, int64_t capacity_out, int32_t cin, int32_t cout, void* d_out,
+                                   void* stream) {
   if (!ctx) return EMC2_ERR_INVALID_ARG;
   if (!d_in || !d_w || !d_nbr || !d_n_out || !d_out)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: null argument");
@@ -173,6 +174,8 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: bad dtype");
   if (w_layout != EMC2_W_PLAIN && w_layout != EMC2_W_PACKED)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: bad weight layout");
+  if (map_hint != EMC2_MAP_ANY && map_hint != EMC2_CONV_SUBM && map_hint != EMC2_CONV_STRIDED)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: bad map_hint");
   const bool mfma = emc2_spconv_uses_mfma(dtype, cin, cout) != 0;
   if (w_layout == EMC2_W_PACKED && !mfma)
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: packed weights need an MFMA-covered (dtype, Cin, Cout)");
@@ -183,8 +186,13 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
       emc2_spconv_mfma_pack(d_w, cin, cout, ctx->wpack, s);  // stream order protects the shared scratch
       wp = ctx->wpack;
     }
-    emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out,
-                            s);
+    // the span-gather kernel pays where the three kx taps of a group name nearly the same rows
+    if (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout))
+      emc2_spconv_span_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
+                              d_out, s);
+    else
+      emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
+                              d_out, s);
   } else if (dtype == EMC2_F32) {
     launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
   } else if (dtype == EMC2_F16) {

@@ -15,3 +15,11 @@ void emc2_spconv_mfma_pack(const void* d_w, int cin, int cout, void* d_packed, h
 void emc2_spconv_mfma_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                              const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
                              int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream);
+
+// Span-gather variant (one contiguous fetch of input rows per group of three kx taps): profitable for
+// kernel maps whose three kx taps name nearly the same rows (submanifold maps over voxels sorted by key).
+// Same arguments and results as emc2_spconv_mfma_launch.
+bool emc2_spconv_span_supported(int cin, int cout);
+void emc2_spconv_span_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
+                             const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
+                             int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream);

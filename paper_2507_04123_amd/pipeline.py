@@ -158,7 +158,7 @@ class BranchRunner:
             with tm(("conv", li)):
                 ctx.spconv(self.dtype, x, self.wdev[li][0], p["scale"] if has_epi else None,
                            p["shift"] if has_epi else None, layer.epilogue, nbr, lv.n, lv.cap, y,
-                           w_layout=self.wdev[li][1])
+                           w_layout=self.wdev[li][1], map_hint=layer.kind)
             x = y
         return x
 

@@ -236,7 +236,7 @@ def test_kmap_configs_full_size(cfg_index):
 # sparse conv
 # ------------------------------------------------------------------------------------------------
 
-def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None, packed=False):
+def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None, packed=False, hint=B.MAP_ANY):
     n_out = nbr_np.shape[1]
     cap = cap or max(n_out, 1)
     nbr = torch.full((27, cap), -1, dtype=torch.int32, device="cuda")
@@ -251,7 +251,7 @@ def gpu_spconv(ctx, dtype, x_np, w_np, scale, shift, epi, nbr_np, cap=None, pack
         ctx.pack_weights(dtype, w, wp)
         w, layout = wp, B.W_PACKED
     ctx.spconv(dtype, x, w, None if scale is None else dev(scale), None if shift is None else dev(shift), epi, nbr, n_t,
-               cap, out, w_layout=layout)
+               cap, out, w_layout=layout, map_hint=hint)
     torch.cuda.synchronize()
     return out
 
@@ -292,12 +292,50 @@ def test_spconv_subm_and_strided_small(dtype, cin, cout, grid, n, epi):
         cap = nbr.shape[1] + 37                                  # capacity beyond n_out: tail must stay untouched
         layouts = [False, True] if ctx.uses_mfma(dtype, cin, cout) else [False]
         for packed in layouts:
-            got = gpu_spconv(ctx, dtype, x, w, scale, shift, epi, nbr, cap=cap, packed=packed)
-            assert_features_close(got[:nbr.shape[1]].float().cpu().numpy(), exp, RTOL[dtype], f"spconv {cin}->{cout}")
-            assert torch.all(got[nbr.shape[1]:].float() == 768.0)
+            # the hint selects a kernel, never a result: every table runs under every hint
+            for hint in ((B.MAP_ANY, SUBM, STRIDED) if packed else (kind,)):
+                got = gpu_spconv(ctx, dtype, x, w, scale, shift, epi, nbr, cap=cap, packed=packed, hint=hint)
+                assert_features_close(got[:nbr.shape[1]].float().cpu().numpy(), exp, RTOL[dtype],
+                                      f"spconv {cin}->{cout} hint={hint}")
+                assert torch.all(got[nbr.shape[1]:].float() == 768.0)
     if not ctx.uses_mfma(dtype, cin, cout) and dtype != F32:
         with pytest.raises(B.Emc2Error):                         # packed layout only exists for MFMA shapes
             ctx.pack_weights(dtype, dev(w, TD[dtype]), torch.empty_like(dev(w, TD[dtype])))
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_spconv_arbitrary_table_under_every_hint(dtype):
+    """A table with no structure at all (random rows, random gaps, not ascending) and one whose groups span
+    just under / just over the row interval a submanifold-tuned kernel can hold: same results under any hint."""
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    cin = cout = 64
+    n_in, n_out = 2000, 1357                                     # several 512-row blocks and a ragged tail
+    st = gen.Stream(4242 + dtype, 9)
+    x = gen.round_to_dtype(st.normal(n_in * cin).astype(np.float32).reshape(-1, cin), dtype)
+    w = gen.round_to_dtype(st.normal(27 * cin * cout, 0.1).astype(np.float32).reshape(27, cin, cout), dtype)
+    scale = (st.uniform(cout, 0.8, 1.2) / (0.1 * np.sqrt(9.0 * cin))).astype(np.float32)
+    shift = st.uniform(cout, -0.1, 0.1).astype(np.float32)
+    rnd = (st.bits(27 * n_out) % np.uint64(n_in)).astype(np.int32).reshape(27, n_out)
+    keep = st.uniform(27 * n_out, 0.0, 1.0).reshape(27, n_out) < 0.4
+    random_table = np.where(keep, rnd, -1).astype(np.int32)
+    # ascending tables whose 64-row groups span `width` input rows: row r reads r*width/64 + kx
+    tables = {"random": random_table}
+    for width in (60, 78, 79, 80, 81, 96, 200):
+        t = -np.ones((27, n_out), np.int32)
+        r = np.arange(n_out)
+        base = (r // 64) * 64 + ((r % 64) * (width - 3)) // 63
+        for k in range(27):
+            t[k] = np.minimum(base + (k % 3), n_in - 1)
+        t[:, ::7] = -1
+        tables[f"span{width}"] = t
+    for name, nbr in tables.items():
+        print(f"spconv arbitrary table {name} dtype={dtype}", flush=True)
+        exp = oracle.spconv(x, w, scale, shift, EPI_AFFINE_RELU, nbr)
+        for hint in (B.MAP_ANY, SUBM, STRIDED):
+            got = gpu_spconv(ctx, dtype, x, w, scale, shift, EPI_AFFINE_RELU, nbr, cap=n_out + 5, packed=True, hint=hint)
+            assert_features_close(got[:n_out].float().cpu().numpy(), exp, RTOL[dtype], f"{name} hint={hint}")
+            assert torch.all(got[n_out:].float() == 768.0)
     ctx.close()
 
 
@@ -308,8 +346,10 @@ def test_spconv_empty_and_all_absent():
     assert torch.all(got.float() == 768.0)
     nbr = -np.ones((27, 100), np.int32)
     shift = np.full(64, 0.25, np.float32)
-    got = gpu_spconv(ctx, F16, np.ones((3, 64), np.float32), w + 1, np.ones(64, np.float32), shift, EPI_AFFINE, nbr)
-    assert torch.all(got.float() == 0.25)                         # no neighbour at all: acc = 0 -> shift
+    for hint in (B.MAP_ANY, SUBM):
+        got = gpu_spconv(ctx, F16, np.ones((3, 64), np.float32), w + 1, np.ones(64, np.float32), shift, EPI_AFFINE, nbr,
+                         hint=hint)
+        assert torch.all(got.float() == 0.25)                     # no neighbour at all: acc = 0 -> shift
     ctx.close()
 
 
