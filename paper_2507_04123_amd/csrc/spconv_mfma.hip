@@ -112,7 +112,14 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
   constexpr int CH = CIN / 8;                 // 16-byte chunks per feature row
   constexpr int RPI = 64 / CH;                // rows covered by one staging load instruction
   constexpr int NI = R / RPI;                 // staging load instructions per tap
-  constexpr int ROW16 = CH + 1;               // LDS row pitch in 16-byte units (one unit of padding)
+  // LDS tile layout, in 16-byte units.  The LDS serves a 16-byte write instruction 8 lanes at a time over
+  // 32 banks and a 16-byte read 16 lanes at a time over 64 banks.  Rows of 128 bytes or more get one unit
+  // of padding (8 lanes write half a row or more; 16 lanes read one piece of 16 consecutive rows: distinct
+  // banks).  Shorter rows are stored unpadded with their pieces XOR-swizzled by the row number: padding
+  // would make the 2 or 4 rows that 8 lanes write overlap modulo 32 banks.
+  constexpr bool SWZ = CH <= 4;
+  constexpr int ROW16 = SWZ ? CH : CH + 1;
+  constexpr int SWSH = CH == 4 ? 2 : 3;       // swizzle key of row r: (r >> SWSH) & (CH - 1)
   constexpr int D = Pipe<CIN, COUT>::D;
   constexpr int WD = Pipe<CIN, COUT>::WD;
   constexpr int NB = Pipe<CIN, COUT>::NB;
@@ -219,7 +226,7 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
       // loads stay unconditional (see above), only their use is skipped (wave-uniform branch)
       if (!Pipe<CIN, COUT>::SKIP || mask != 0ull) {
 #pragma unroll
-        for (int i = 0; i < NI; ++i) my_tile[(i * RPI + srow) * ROW16 + schunk] = sreg[kx % D][i];
+        for (int i = 0; i < NI; ++i) my_tile[(i * RPI + srow) * ROW16 + (SWZ ? (schunk ^ (((i * RPI + srow) >> SWSH) & (CH - 1))) : schunk)] = sreg[kx % D][i];
       }
       // the freed register set takes the gather of tap + D (absent entries re-read row 0 and are masked)
       const int32_t past = g < 8 ? 0 : -1;   // entries of "group 9" do not exist
@@ -239,8 +246,9 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
           u32x4 b[NT];
 #pragma unroll
           for (int j = 0; j < NT; ++j) b[j] = wb[(t * NT + j) * 64 + lane];
-          u32x4 a0 = my_tile[m * ROW16 + 2 * t + h];
-          u32x4 a1 = my_tile[(32 + m) * ROW16 + 2 * t + h];
+          const int ca = SWZ ? ((2 * t + h) ^ ((m >> SWSH) & (CH - 1))) : 2 * t + h;   // rows m and 32 + m share a key
+          u32x4 a0 = my_tile[m * ROW16 + ca];
+          u32x4 a1 = my_tile[(32 + m) * ROW16 + ca];
           a0 = v0 ? a0 : u32x4{0u, 0u, 0u, 0u};
           a1 = v1 ? a1 : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
