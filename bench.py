@@ -86,6 +86,19 @@ def cpu_baseline(cfg, pts, seed, threads):
             "ms_per_frame": dt * 1e3}
 
 
+def profiled_traffic(kernel, config_index):
+    """HBM bytes per launch of `kernel` from the committed counter summary (rocprofv3 --pmc FETCH_SIZE and
+    WRITE_SIZE runs of this same bench, scaled by a known-size copy); None if no summary covers it."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_config{config_index}_pmc_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -180,7 +193,8 @@ def main() -> int:
             stage_ms[tag] = stage_ms.get(tag, 0.0) + ms
     groups = {}
     for li, layer in enumerate(br.layers):
-        g = groups.setdefault((layer.cin, layer.cout), {"ms": 0.0, "layers": []})
+        kname = ctx.spconv_kernel(cfg.dtype, layer.cin, layer.cout, layer.kind)
+        g = groups.setdefault((kname, layer.cin, layer.cout), {"ms": 0.0, "layers": []})
         g["ms"] += conv_ms[li]
         g["layers"].append(li)
     dom_key = max(groups, key=lambda k: groups[k]["ms"])
@@ -208,12 +222,12 @@ def main() -> int:
         dom_launches += 1
     achieved_tflops = dom_flops_total / (dom_ms_total * 1e-3) / 1e12 if dom_ms_total > 0 else 0.0
     roofline = {
-        "kernel": f"k_spconv_mfma<f16, Cin={dom_key[0]}, Cout={dom_key[1]}>",
+        "kernel": f"{dom_key[0]}<f16, Cin={dom_key[1]}, Cout={dom_key[2]}>",
         "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved_tflops / PEAK_MFMA_F16_TFLOPS,
         "flops_per_launch": dom_flops_total / max(dom_launches, 1), "launches_per_step": len(dom_layers),
         "avg_launch_ms": dom_ms_total / max(dom_launches, 1), "launches_timed": dom_launches,
-        "traffic": None,
+        "traffic": profiled_traffic(dom_key[0], cfg.index),
     }
 
     total_flops = sum(layer_flops)

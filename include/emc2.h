@@ -167,6 +167,12 @@ emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, 
  *   taps of a (dz, dy) pair share one fetch of input rows): results do not depend on it, for any table.
  */
 #define EMC2_MAP_ANY (-1)
+/*
+ * Name of the device kernel emc2_spconv launches for these arguments ("k_spconv_span", "k_spconv_mfma",
+ * "k_spconv_small" or "k_spconv_alu"): lets a profile be matched to a layer.  Host-only query; the
+ * string is static.  NULL for a dtype emc2_spconv rejects.
+ */
+const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t cout, int32_t map_hint);
 emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w, emc2_wlayout w_layout,
                         const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
                         const int32_t* d_nbr, int32_t map_hint, const int32_t* d_n_out, int64_t capacity_out,

@@ -27,7 +27,8 @@ MAP_ANY = -1   # emc2_spconv map_hint: SUBM / STRIDED as passed to build_kmap, o
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
-           "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma"]
+           "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
+           "emc2_spconv_kernel"]
 
 
 class Emc2Error(RuntimeError):
@@ -72,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, i32, vp, i64, i32, i32, vp, vp]
     lib.emc2_pack_weights.restype = ctypes.c_int
     lib.emc2_pack_weights.argtypes = [vp, ctypes.c_int, vp, i32, i32, vp, vp]
+    lib.emc2_spconv_kernel.restype = ctypes.c_char_p
+    lib.emc2_spconv_kernel.argtypes = [ctypes.c_int, i32, i32, i32]
     lib.emc2_spconv_uses_mfma.restype = i32
     lib.emc2_spconv_uses_mfma.argtypes = [ctypes.c_int, i32, i32]
     lib.emc2_project_gather.restype = ctypes.c_int
@@ -189,6 +192,10 @@ class Context:
             raise ValueError("w must be [27][Cin][Cout] and packed the same size")
         self._chk(self.lib.emc2_pack_weights(self.h, dtype, _ptr(w), int(w.shape[1]), int(w.shape[2]), _ptr(packed),
                                              _stream()))
+
+    def spconv_kernel(self, dtype: int, cin: int, cout: int, map_hint: int = MAP_ANY) -> str:
+        """Name of the device kernel `spconv` launches for these arguments (for matching profiles to layers)."""
+        return self.lib.emc2_spconv_kernel(dtype, cin, cout, map_hint).decode()
 
     def spconv(self, dtype: int, x: torch.Tensor, w: torch.Tensor, scale: Optional[torch.Tensor],
                shift: Optional[torch.Tensor], epilogue: int, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int,

@@ -144,6 +144,15 @@ extern "C" int32_t emc2_spconv_uses_mfma(emc2_dtype dtype, int32_t cin, int32_t 
   return (dtype == EMC2_F16 || dtype == EMC2_BF16) && emc2_spconv_mfma_supported(cin, cout) ? 1 : 0;
 }
 
+static bool small_covers(int cin, int cout) { return (cin == 4 && (cout == 16 || cout == 32)) || (cin == 16 && cout == 16); }
+
+extern "C" const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t cout, int32_t map_hint) {
+  if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16) return nullptr;
+  if (emc2_spconv_uses_mfma(dtype, cin, cout))
+    return (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout)) ? "k_spconv_span" : "k_spconv_mfma";
+  return small_covers(cin, cout) ? "k_spconv_small" : "k_spconv_alu";
+}
+
 extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, int32_t cin, int32_t cout,
                                          void* d_packed, void* stream) {
   if (!ctx) return EMC2_ERR_INVALID_ARG;
