@@ -5,16 +5,22 @@
 
 namespace {
 
-__global__ void __launch_bounds__(256) k_index_clear(uint4* __restrict__ p, int64_t n16) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
-    p[i] = make_uint4(0u, 0u, 0u, 0u);
+// One block per tile: a flagged tile is zeroed (16 KB) and its flag lowered; the others cost one load.
+__global__ void __launch_bounds__(256) k_index_clear(uint4* __restrict__ p, uint32_t* __restrict__ flags) {
+  const uint32_t f = flags[blockIdx.x];
+  if (!f) return;  // uniform for the block
+  uint4* t = p + (int64_t)blockIdx.x * (EMC2_SCAN_TILE / 2);
+#pragma unroll
+  for (int i = 0; i < EMC2_SCAN_TILE / 2 / 256; ++i) t[i * 256 + threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
+  __syncthreads();  // every thread has read the flag
+  if (threadIdx.x == 0) flags[blockIdx.x] = 0u;
 }
 
 __global__ void __launch_bounds__(256) k_index_mark_coords(cellword_t* __restrict__ idx,
                                                            const int4* __restrict__ coords,
                                                            const int32_t* __restrict__ d_n, int64_t capacity,
-                                                           int gx, int gy, int gz, int n_batch) {
+                                                           int gx, int gy, int gz, int n_batch,
+                                                           uint32_t* __restrict__ flags) {
   int64_t n = *d_n;
   if (n > capacity) n = capacity;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -25,6 +31,7 @@ __global__ void __launch_bounds__(256) k_index_mark_coords(cellword_t* __restric
     return;  // malformed coordinate: ignore rather than write out of bounds
   const uint64_t key = (((uint64_t)c.x * gz + (uint64_t)c.y) * gy + (uint64_t)c.z) * gx + (uint64_t)c.w;
   atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
 }
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
@@ -38,7 +45,12 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
 
 // Per-block popcount totals.  Thread t owns the 8 consecutive words [8t, 8t+8) of its tile.
 __global__ void __launch_bounds__(256) k_scan_reduce(const cellword_t* __restrict__ idx, int64_t n_words,
-                                                     uint32_t* __restrict__ partials) {
+                                                     uint32_t* __restrict__ partials,
+                                                     const uint32_t* __restrict__ flags) {
+  if (!flags[blockIdx.x]) {  // no bit in this tile (uniform for the block)
+    if (threadIdx.x == 0) partials[blockIdx.x] = 0u;
+    return;
+  }
   const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
   uint32_t s = 0;
 #pragma unroll
@@ -86,7 +98,9 @@ __global__ void __launch_bounds__(1024) k_scan_partials(uint32_t* __restrict__ p
 
 // Write each word's exclusive prefix (.y).
 __global__ void __launch_bounds__(256) k_scan_apply(cellword_t* __restrict__ idx, int64_t n_words,
-                                                    const uint32_t* __restrict__ partials) {
+                                                    const uint32_t* __restrict__ partials,
+                                                    const uint32_t* __restrict__ flags) {
+  if (!flags[blockIdx.x]) return;  // no bit, so no prefix field anybody reads
   const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
   uint32_t bits[8];
   uint32_t s = 0;
@@ -144,7 +158,11 @@ __global__ void __launch_bounds__(1024) k_scan_small(cellword_t* __restrict__ id
 // sums totals[0..b) cooperatively.  Quadratic in the number of blocks, so only used while that is small.
 __global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict__ idx, int64_t n_words,
                                                          const uint32_t* __restrict__ totals, int64_t capacity,
-                                                         int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags) {
+                                                         int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags,
+                                                         const uint32_t* __restrict__ flags) {
+  // a tile without bits has no prefix field anybody reads; the last block still reports the total
+  const bool has_bits = flags[blockIdx.x] != 0u;
+  if (!has_bits && blockIdx.x != gridDim.x - 1) return;  // uniform for the block
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t base_s;
   uint32_t part = 0;
@@ -161,7 +179,7 @@ __global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict_
   uint32_t s = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    bits[j] = (base + j < n_words) ? idx[base + j].x : 0u;
+    bits[j] = (has_bits && base + j < n_words) ? idx[base + j].x : 0u;
     s += __popc(bits[j]);
   }
   const uint32_t inc = wave_inclusive_scan(s);
@@ -173,7 +191,7 @@ __global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict_
   for (int j = 0; j < w; ++j) run += wsum[j];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    if (base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
+    if (has_bits && base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
     run += __popc(bits[j]);
   }
   if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 255) {
@@ -188,22 +206,16 @@ __global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict_
 
 }  // namespace
 
-void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, hipStream_t stream) {
-  (void)ctx;
-  const int64_t n_words = emc2_div_up(n_cells, 32);
-  const int64_t n16 = emc2_div_up(n_words, 2);  // slot has one spare word, so rounding up is in bounds
-  int64_t blocks = emc2_div_up(n16, 256 * 4);
-  if (blocks < 1) blocks = 1;
-  if (blocks > 65536) blocks = 65536;
-  hipLaunchKernelGGL(k_index_clear, dim3((unsigned)blocks), dim3(256), 0, stream, (uint4*)idx, n16);
+void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, hipStream_t stream) {
+  hipLaunchKernelGGL(k_index_clear, dim3((unsigned)ctx->slot_tiles), dim3(256), 0, stream, (uint4*)idx,
+                     emc2_slot_flags(ctx, idx));
 }
 
 void emc2_index_mark_coords(emc2_ctx* ctx, cellword_t* idx, const int32_t* d_coords, const int32_t* d_n,
                             int64_t capacity, const int32_t grid[3], int32_t n_batch, hipStream_t stream) {
-  (void)ctx;
   if (capacity < 1) return;
   hipLaunchKernelGGL(k_index_mark_coords, dim3((unsigned)emc2_div_up(capacity, 256)), dim3(256), 0, stream, idx,
-                     (const int4*)d_coords, d_n, capacity, grid[0], grid[1], grid[2], n_batch);
+                     (const int4*)d_coords, d_n, capacity, grid[0], grid[1], grid[2], n_batch, emc2_slot_flags(ctx, idx));
 }
 
 void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t capacity, int32_t* d_total,
@@ -215,13 +227,15 @@ void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t ca
     hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, stream, idx, n_words, capacity, d_total, ctx->dev_words);
     return;
   }
-  hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);
+  hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
+                     emc2_slot_flags(ctx, idx));
   if (n_blocks <= 2048) {
     hipLaunchKernelGGL(k_scan_apply_self, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
-                       capacity, d_total, ctx->dev_words);
+                       capacity, d_total, ctx->dev_words, emc2_slot_flags(ctx, idx));
     return;
   }
   hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(1024), 0, stream, ctx->partials, n_blocks, capacity, d_total,
                      ctx->dev_words);
-  hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials);
+  hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
+                     emc2_slot_flags(ctx, idx));
 }

@@ -66,7 +66,8 @@ struct emc2_ctx {
   int device;
   int64_t max_points, max_voxels, max_cells;
   int32_t n_slots;          // user-visible slots; two more internal ones follow
-  int64_t slot_words;       // cellwords per slot
+  int64_t slot_words;       // cellwords per slot (a whole number of tiles); the tile flags follow them
+  int64_t slot_tiles;
   cellword_t** slots;       // host array [n_slots + 2] of device pointers
   SlotMeta* meta;           // host array [n_slots + 2]
   VoxRec* table;            // [table_slots]
@@ -81,6 +82,16 @@ struct emc2_ctx {
 };
 
 #define EMC2_SCAN_TILE 2048  // cellwords per scan block (256 threads x 8)
+#define EMC2_TILE_SHIFT 11   // log2(EMC2_SCAN_TILE)
+
+// Tile flags of an index slot.  The active cells of a LiDAR frame fill a fraction of a percent of the
+// finest grid, so every index slot carries one flag per 2048-word tile, stored behind its words:
+// INVARIANT: a tile whose flag is 0 holds no occupancy bit (its prefix fields are unspecified and never
+// read: a lookup tests the bit first).  Every kernel that sets bits raises the flag of the tile it writes;
+// clear, scan and the stride-2 marking skip unflagged tiles instead of streaming the whole grid.
+static inline uint32_t* emc2_slot_flags(const emc2_ctx* ctx, cellword_t* idx) {
+  return reinterpret_cast<uint32_t*>(idx + ctx->slot_words);
+}
 
 // host helpers (context.hip)
 emc2_status emc2_fail(emc2_ctx* ctx, emc2_status st, const char* fmt, ...);
@@ -88,7 +99,8 @@ emc2_status emc2_check_hip(emc2_ctx* ctx, hipError_t e, const char* what);
 bool emc2_grid_ok(const int32_t grid[3], int32_t n_batch, int64_t* n_cells);
 
 // cell-index construction (cellindex.hip); all asynchronous on `stream`
-void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, hipStream_t stream);
+// zero every flagged tile of the slot (whatever grid it last held) and lower its flag
+void emc2_index_clear(emc2_ctx* ctx, cellword_t* idx, hipStream_t stream);
 // exclusive scan of popcounts over ceil(n_cells/32) words; writes min(total, capacity) to d_total
 // and raises EMC2_DEVFLAG_CAPACITY when total > capacity
 void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t capacity, int32_t* d_total,

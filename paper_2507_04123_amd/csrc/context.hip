@@ -60,12 +60,17 @@ extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_point
     if (st != EMC2_OK) goto fail;                         \
   } while (0)
   TRY(hipSetDevice(device), "hipSetDevice");
-  ctx->slot_words = emc2_div_up(max_cells, 32) + 1;
+  // one spare word (a stride-2 mark may spill one word past the grid), rounded up to whole tiles
+  ctx->slot_tiles = emc2_div_up(emc2_div_up(max_cells, 32) + 1, EMC2_SCAN_TILE);
+  ctx->slot_words = ctx->slot_tiles * EMC2_SCAN_TILE;
   ctx->slots = (cellword_t**)calloc((size_t)n_slots + 2, sizeof(cellword_t*));
   ctx->meta = (SlotMeta*)calloc((size_t)n_slots + 2, sizeof(SlotMeta));
   if (!ctx->slots || !ctx->meta) { st = EMC2_ERR_DEVICE; goto fail; }
-  for (int s = 0; s < n_slots + 2; ++s)
-    TRY(hipMalloc((void**)&ctx->slots[s], sizeof(cellword_t) * (size_t)ctx->slot_words), "hipMalloc(index slot)");
+  for (int s = 0; s < n_slots + 2; ++s) {
+    const size_t bytes = sizeof(cellword_t) * (size_t)ctx->slot_words + sizeof(uint32_t) * (size_t)ctx->slot_tiles;
+    TRY(hipMalloc((void**)&ctx->slots[s], bytes), "hipMalloc(index slot)");
+    TRY(hipMemset(ctx->slots[s], 0, bytes), "hipMemset(index slot)");  // establishes the tile-flag invariant
+  }
   // the hash holds at most one entry per point and at most max_voxels useful ones; twice that many slots
   ctx->table_slots = pow2_at_least(2 * (max_points < max_voxels ? max_points : max_voxels));
   if (ctx->table_slots < 1024) ctx->table_slots = 1024;

@@ -28,9 +28,12 @@ __device__ __forceinline__ uint32_t compress_even_bits(uint64_t v) {
 // words instead of voxels turns hundreds of colliding single-bit atomics per output word into a few.
 __global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restrict__ in_idx, int64_t n_in_words,
                                                       int64_t n_in_cells, cellword_t* __restrict__ out_idx, int gx, int gy,
-                                                      int gz, int gox, int goy, int goz) {
+                                                      int gz, int gox, int goy, int goz,
+                                                      const uint32_t* __restrict__ in_flags,
+                                                      uint32_t* __restrict__ out_flags) {
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_in_words) return;
+  if (!in_flags[w >> EMC2_TILE_SHIFT]) return;   // no bit in this tile of the input (uniform for the wave)
   uint32_t bits = in_idx[w].x;
   while (bits) {
     // row segment of the word that starts at the first set bit's row
@@ -61,7 +64,11 @@ __global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restri
         const uint64_t okey = ((b * goz + (uint64_t)(z0 + dz)) * goy + (uint64_t)(y0 + dy)) * gox + (uint64_t)ob;
         const uint32_t sh = (uint32_t)okey & 31u;
         atomicOr(&out_idx[okey >> 5].x, m << sh);
-        if (sh != 0 && (m >> (32u - sh)) != 0) atomicOr(&out_idx[(okey >> 5) + 1].x, m >> (32u - sh));
+        out_flags[okey >> (5 + EMC2_TILE_SHIFT)] = 1u;
+        if (sh != 0 && (m >> (32u - sh)) != 0) {
+          atomicOr(&out_idx[(okey >> 5) + 1].x, m >> (32u - sh));
+          out_flags[((okey >> 5) + 1) >> EMC2_TILE_SHIFT] = 1u;
+        }
       }
   }
 }
@@ -212,7 +219,7 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
   } else {
     // rebuild the input index from the (ascending, distinct) coordinates; ranks then equal positions
     in_idx = ctx->slots[tmp_in];
-    emc2_index_clear(ctx, in_idx, cells_in, s);
+    emc2_index_clear(ctx, in_idx, s);
     emc2_index_mark_coords(ctx, in_idx, d_in_coords, d_n_in, capacity_in, grid_in, n_batch, s);
     emc2_index_scan(ctx, in_idx, cells_in, capacity_in, ctx->dev_words + 2, s);
   }
@@ -238,11 +245,12 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
       m.n_batch = n_batch;
       m.valid = true;
     }
-    emc2_index_clear(ctx, out_idx, cells_out, s);
+    emc2_index_clear(ctx, out_idx, s);
     {
       const int64_t n_in_words = emc2_div_up(cells_in, 32);
       hipLaunchKernelGGL(k_strided_mark, dim3((unsigned)emc2_div_up(n_in_words, 256)), dim3(256), 0, s, in_idx, n_in_words,
-                         cells_in, out_idx, grid_in[0], grid_in[1], grid_in[2], go[0], go[1], go[2]);
+                         cells_in, out_idx, grid_in[0], grid_in[1], grid_in[2], go[0], go[1], go[2],
+                         emc2_slot_flags(ctx, in_idx), emc2_slot_flags(ctx, out_idx));
     }
     emc2_index_scan(ctx, out_idx, cells_out, capacity_out, d_n_out, s);
     const int64_t n_words = emc2_div_up(cells_out, 32);

@@ -56,7 +56,7 @@ __global__ void __launch_bounds__(256) k_vox_insert(const float* __restrict__ po
                                                     int64_t n_points, VoxParams prm, VoxRec* __restrict__ table,
                                                     uint32_t slot_mask, cellword_t* __restrict__ idx,
                                                     int32_t* __restrict__ uslot, int64_t capacity,
-                                                    int32_t* __restrict__ dev_words) {
+                                                    int32_t* __restrict__ dev_words, uint32_t* __restrict__ flags) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   bool keep = i < n_points;
   float px = 0.f, py = 0.f, pz = 0.f, pi = 0.f;
@@ -114,6 +114,7 @@ __global__ void __launch_bounds__(256) k_vox_insert(const float* __restrict__ po
       if (id < capacity) uslot[id] = (int32_t)slot;
       else atomicOr(&dev_words[0], EMC2_DEVFLAG_CAPACITY);
       atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+      flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;   // this tile of the index now holds a bit
     }
   }
 }
@@ -199,7 +200,7 @@ extern "C" emc2_status emc2_voxelize(emc2_ctx* ctx, const float* d_points, const
   prm.r2_max = spec->r2_max;
   prm.stride_f = spec->stride_f;
 
-  emc2_index_clear(ctx, idx, n_cells, s);
+  emc2_index_clear(ctx, idx, s);
   {
     int64_t blocks = emc2_div_up(2 * n_rec, 256 * 4);
     if (blocks > 65536) blocks = 65536;
@@ -207,7 +208,8 @@ extern "C" emc2_status emc2_voxelize(emc2_ctx* ctx, const float* d_points, const
   }
   if (n_points > 0)
     hipLaunchKernelGGL(k_vox_insert, dim3((unsigned)emc2_div_up(n_points, 256)), dim3(256), 0, s, d_points, d_batch,
-                       n_points, prm, ctx->table, (uint32_t)(n_rec - 1), idx, ctx->uslot, capacity, ctx->dev_words);
+                       n_points, prm, ctx->table, (uint32_t)(n_rec - 1), idx, ctx->uslot, capacity, ctx->dev_words,
+                       emc2_slot_flags(ctx, idx));
   emc2_index_scan(ctx, idx, n_cells, capacity, d_n_voxels, s);
   {
     // at most min(n_points, capacity) distinct voxels were listed
