@@ -77,6 +77,7 @@ struct emc2_ctx {
   int64_t n_partials;
   int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count
   void* wpack;              // scratch for weights re-ordered per call (27*128*128 16-bit values)
+  void* zero_row;           // 256 zero bytes: the feature row an absent neighbour reads
   int32_t* pinned;          // pinned host staging for counts / status (4 ints)
   char err[256];
 };

@@ -78,6 +78,8 @@ extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_point
   TRY(hipMalloc((void**)&ctx->uslot, sizeof(int32_t) * (size_t)max_voxels), "hipMalloc(uslot)");
   ctx->n_partials = emc2_div_up(ctx->slot_words, EMC2_SCAN_TILE) + 1;
   TRY(hipMalloc((void**)&ctx->partials, sizeof(uint32_t) * (size_t)ctx->n_partials), "hipMalloc(partials)");
+  TRY(hipMalloc((void**)&ctx->zero_row, 256), "hipMalloc(zero_row)");
+  TRY(hipMemset(ctx->zero_row, 0, 256), "hipMemset(zero_row)");
   TRY(hipMalloc((void**)&ctx->wpack, (size_t)27 * 128 * 128 * 2), "hipMalloc(wpack)");
   TRY(hipMalloc((void**)&ctx->dev_words, sizeof(int32_t) * 8), "hipMalloc(dev_words)");
   TRY(hipMemset(ctx->dev_words, 0, sizeof(int32_t) * 8), "hipMemset(dev_words)");
@@ -103,6 +105,7 @@ extern "C" void emc2_destroy(emc2_ctx* ctx) {
   if (ctx->table) (void)hipFree(ctx->table);
   if (ctx->uslot) (void)hipFree(ctx->uslot);
   if (ctx->partials) (void)hipFree(ctx->partials);
+  if (ctx->zero_row) (void)hipFree(ctx->zero_row);
   if (ctx->wpack) (void)hipFree(ctx->wpack);
   if (ctx->dev_words) (void)hipFree(ctx->dev_words);
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);

@@ -148,8 +148,10 @@ static bool small_covers(int cin, int cout) { return (cin == 4 && (cout == 16 ||
 
 extern "C" const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t cout, int32_t map_hint) {
   if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16) return nullptr;
-  if (emc2_spconv_uses_mfma(dtype, cin, cout))
-    return (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout)) ? "k_spconv_span" : "k_spconv_mfma";
+  if (emc2_spconv_uses_mfma(dtype, cin, cout)) {
+    if (!emc2_spconv_direct_supported(cin, cout)) return "k_spconv_mfma";
+    return (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout)) ? "k_spconv_span" : "k_spconv_direct";
+  }
   return small_covers(cin, cout) ? "k_spconv_small" : "k_spconv_alu";
 }
 
@@ -160,7 +162,12 @@ extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const 
   if (!emc2_spconv_uses_mfma(dtype, cin, cout))
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_pack_weights: (dtype, Cin=%d, Cout=%d) does not use the MFMA path", cin,
                      cout);
-  emc2_spconv_mfma_pack(d_w, cin, cout, d_packed, (hipStream_t)stream);
+  // the fragment order is a function of (Cin, Cout) alone: whichever kernel a call later selects for this
+  // shape reads the same packed weights
+  if (emc2_spconv_direct_supported(cin, cout))
+    emc2_spconv_direct_pack(d_w, cin, cout, d_packed, (hipStream_t)stream);
+  else
+    emc2_spconv_mfma_pack(d_w, cin, cout, d_packed, (hipStream_t)stream);
   return emc2_check_hip(ctx, hipGetLastError(), "emc2_pack_weights launch");
 }
 
@@ -190,18 +197,24 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: packed weights need an MFMA-covered (dtype, Cin, Cout)");
   hipStream_t s = (hipStream_t)stream;
   if (mfma) {
+    const bool direct = emc2_spconv_direct_supported(cin, cout);
     const void* wp = d_w;
     if (w_layout == EMC2_W_PLAIN) {
-      emc2_spconv_mfma_pack(d_w, cin, cout, ctx->wpack, s);  // stream order protects the shared scratch
+      // stream order protects the shared scratch
+      if (direct) emc2_spconv_direct_pack(d_w, cin, cout, ctx->wpack, s);
+      else emc2_spconv_mfma_pack(d_w, cin, cout, ctx->wpack, s);
       wp = ctx->wpack;
     }
-    // the span-gather kernel pays where the three kx taps of a group name nearly the same rows
-    if (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout))
+    if (!direct)
+      emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
+                              d_out, s);
+    else if (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout))
+      // pays where the three kx taps of a group name nearly the same rows
       emc2_spconv_span_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
                               d_out, s);
     else
-      emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
-                              d_out, s);
+      emc2_spconv_direct_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
+                                ctx->zero_row, d_out, s);
   } else if (dtype == EMC2_F32) {
     launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
   } else if (dtype == EMC2_F16) {

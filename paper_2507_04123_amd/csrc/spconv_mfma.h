@@ -23,3 +23,13 @@ bool emc2_spconv_span_supported(int cin, int cout);
 void emc2_spconv_span_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                              const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
                              int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream);
+
+// Register-direct variant (A operands straight from global memory, 16x16x32 MFMA; LDS holds weights only).
+// Its packed weight layout differs from the other kernels': shapes it supports are packed by
+// emc2_spconv_direct_pack and always run on it.  d_zero_row: >= 256 zero bytes in device memory.
+bool emc2_spconv_direct_supported(int cin, int cout);
+void emc2_spconv_direct_pack(const void* d_w, int cin, int cout, void* d_packed, hipStream_t stream);
+void emc2_spconv_direct_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
+                               const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
+                               int64_t capacity_out, int cin, int cout, const void* d_zero_row, void* d_out,
+                               hipStream_t stream);

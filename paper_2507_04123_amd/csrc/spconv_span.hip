@@ -28,19 +28,20 @@ namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // native vector: real loads and stores
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 template <int DT> struct MmaS;
 template <> struct MmaS<EMC2_F16> {
-  static __device__ __forceinline__ floatx16 run(u32x4 a, u32x4 b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
+  static __device__ __forceinline__ floatx4 run(u32x4 a, u32x4 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint16_t cvt(float v) { return __half_as_ushort(__float2half_rn(v)); }
 };
 template <> struct MmaS<EMC2_BF16> {
-  static __device__ __forceinline__ floatx16 run(u32x4 a, u32x4 b, floatx16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  static __device__ __forceinline__ floatx4 run(u32x4 a, u32x4 b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
   }
   static __device__ __forceinline__ uint16_t cvt(float v) { return __builtin_bit_cast(uint16_t, __float2bfloat16(v)); }
 };
@@ -105,8 +106,9 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
                                           const int32_t* __restrict__ nbr, int64_t n_out, int64_t capacity_out,
                                           uint16_t* __restrict__ out, u32x4* __restrict__ wl, u32x4* __restrict__ my_tile,
                                           int64_t wave_row0) {
-  constexpr int KS = CIN / 16;                // k-steps per tap
-  constexpr int NT = COUT / 32;               // 32-column tiles
+  constexpr int KS = CIN / 32;                // k-steps per tap (v_mfma_f32_16x16x32)
+  constexpr int NT = COUT / 16;               // 16-column tiles
+  constexpr int MT = 4;                       // 16-row tiles per wave
   constexpr int W16 = KS * NT * 64;           // 16-byte weight pieces per tap
   constexpr int G16 = 3 * W16;                // ... per group of three taps
   constexpr int WPT = (G16 + kSpanThreads - 1) / kSpanThreads;
@@ -119,7 +121,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int m = lane & 31, h = lane >> 5;
+  const int m = lane & 15, q = lane >> 4;
   if (lane < ROW16) my_tile[ZROW * ROW16 + lane] = u32x4{0u, 0u, 0u, 0u};
 
   const bool live = wave_row0 + lane < n_out;
@@ -127,13 +129,11 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   const int32_t dead = live ? 0 : -1;               // rows past n_out have no neighbours
   const int srow = lane / CH, schunk = lane % CH;   // gather role: row within an instruction, 16-byte chunk
 
-  floatx16 acc[2][NT];
+  floatx4 acc[MT][NT];
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[mt][j][e] = 0.f;
+    for (int j = 0; j < NT; ++j) acc[mt][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   // kernel-map entries (lane = row) of the group being computed, the next, and (LATE) the one after, as
   // loaded: rows past n_out are masked where the entries are used, never right after the load (that would
@@ -178,31 +178,31 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   if ((GI).span) { EMC2_GATHER_SPAN(GI) } else { EMC2_GATHER_TAP((J)[0]) }
 #define EMC2_TILE_WRITE()                                                                                  \
   _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) my_tile[(i_ * RPI + srow) * ROW16 + schunk] = sreg[i_];
-  // one tap: lane l's LROW is the tile row that output row l of the wave reads
+  // one tap: lane l's LROW is the tile row that output row l of the wave reads.  The A operand of lane
+  // (m, q) for tile mt is 16 bytes at piece 4*ks + q of tile row LROW[16*mt + m]: three lane-swap
+  // instructions broadcast each 16-lane row of LROW to all four rows (no LDS round trip).
 #define EMC2_TAP(KX, LROW, WB)                                                                             \
   {                                                                                                        \
-    const int32_t other_ = __shfl_xor((LROW), 32, 64);                                                     \
-    const int32_t l0_ = h ? other_ : (LROW);                                                               \
-    const int32_t l1_ = h ? (LROW) : other_;                                                               \
-    const u32x4* a0p_ = my_tile + l0_ * ROW16 + h;                                                         \
-    const u32x4* a1p_ = my_tile + l1_ * ROW16 + h;                                                         \
+    const uint32_t lr_ = (uint32_t)(LROW);                                                                 \
+    const u32x2 h_ = __builtin_amdgcn_permlane32_swap(lr_, lr_, false, false);        /* rows 0101 | 2323 */ \
+    const u32x2 lo_ = __builtin_amdgcn_permlane16_swap(h_[0], h_[0], false, false);   /* 0000 | 1111 */    \
+    const u32x2 hi_ = __builtin_amdgcn_permlane16_swap(h_[1], h_[1], false, false);   /* 2222 | 3333 */    \
+    const u32x4* ap_[MT] = {my_tile + lo_[0] * ROW16 + q, my_tile + lo_[1] * ROW16 + q,                    \
+                            my_tile + hi_[0] * ROW16 + q, my_tile + hi_[1] * ROW16 + q};                   \
     _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                       \
-      u32x4 b[NT];                                                                                         \
+      u32x4 b[NT], a[MT];                                                                                  \
       _Pragma("unroll") for (int j = 0; j < NT; ++j) b[j] = (WB)[(((KX) * KS + t) * NT + j) * 64 + lane];  \
-      const u32x4 a0 = a0p_[2 * t];                                                                        \
-      const u32x4 a1 = a1p_[2 * t];                                                                        \
-      _Pragma("unroll") for (int j = 0; j < NT; ++j) {                                                     \
-        acc[0][j] = MmaS<DT>::run(a0, b[j], acc[0][j]);                                                    \
-        acc[1][j] = MmaS<DT>::run(a1, b[j], acc[1][j]);                                                    \
-      }                                                                                                    \
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) a[mt] = ap_[mt][4 * t];                            \
+      _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                    \
+        _Pragma("unroll") for (int j = 0; j < NT; ++j) acc[mt][j] = MmaS<DT>::run(a[mt], b[j], acc[mt][j]); \
     }                                                                                                      \
   }
   // Tile row that output row `lane` reads at tap KX.  Span mode: entry minus lo.  Three-pass mode: the
   // tile holds exactly the rows of the tap being computed, row p for output row p.
 #define EMC2_LROW(KX, C, GI) ((C)[KX] >= 0 ? ((GI).span ? (C)[KX] - (GI).lo : lane) : ZROW)
-  // The matrix instructions sit under no branch at all: with the accumulators live across a branch the
-  // compiler keeps two copies of them and moves 64 registers back and forth at every join.  Only the
-  // memory operations of the (rare) three-pass mode are conditional.
+  // The three taps are straight-line code: with branches between the matrix instructions of a group the
+  // compiler keeps two copies of the accumulators and moves 64 registers back and forth at every join.
+  // Only the memory operations of the (rare) three-pass mode are conditional inside a group.
 #define EMC2_COMPUTE(C, GI, NXT, CNXT, WB)                                                                 \
   {                                                                                                        \
     { const int32_t lrow_ = EMC2_LROW(0, C, GI); EMC2_TAP(0, lrow_, WB) }                                  \
@@ -250,14 +250,20 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
       EMC2_W_LOAD(g + 1)
       if (cur.span) { EMC2_GATHER_MAIN(nxt, c1) } else { EMC2_GATHER_TAP(c0[1]) }
       __builtin_amdgcn_wave_barrier();
-      EMC2_COMPUTE(c0, cur, nxt, c1, wb)
+      // a group none of whose 192 entries is valid costs no LDS read and no matrix instruction
+      if (((cur.valid[0] | cur.valid[1] | cur.valid[2]) != 0ull) || !cur.span) {
+        EMC2_COMPUTE(c0, cur, nxt, c1, wb)
+      }
       __builtin_amdgcn_wave_barrier();
       EMC2_W_STORE((g + 1) & 1)               // weights of group g + 1 -> the LDS buffer group g - 1 used
     } else {
       // tile holds group g (first pass); registers hold the rows of the next pass; wq holds W(g + 1)
       EMC2_MASKED(c2, jq2)
       const GroupInfo aft = analyze<SMAX>(c2);
-      EMC2_COMPUTE(c0, cur, nxt, c1, wb)
+      // a group none of whose 192 entries is valid costs no LDS read and no matrix instruction
+      if (((cur.valid[0] | cur.valid[1] | cur.valid[2]) != 0ull) || !cur.span) {
+        EMC2_COMPUTE(c0, cur, nxt, c1, wb)
+      }
       __builtin_amdgcn_wave_barrier();
       EMC2_W_STORE((g + 1) & 1)
       EMC2_TILE_WRITE()                       // first pass of group g + 1
@@ -294,39 +300,43 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 #undef EMC2_LROW
 #undef EMC2_COMPUTE
 
-  // epilogue: lane holds column n = 32*j + m; acc element e <-> row 8*(e/4) + 4*h + (e%4).  Each 32-row
-  // tile goes through the wave's LDS tile so that the global stores are whole 16-byte pieces of rows.
+  // epilogue: lane (m, q) holds column 16*j + m of rows 16*mt + 4*q + e.  Scale/shift/ReLU/convert in
+  // registers, then each 16-row tile goes through the wave's LDS tile so that the global stores are whole
+  // 16-byte pieces of rows.
   float sc[NT], sh[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
-    sc[j] = (epilogue != EMC2_EPI_NONE) ? scale[32 * j + m] : 1.f;
-    sh[j] = (epilogue != EMC2_EPI_NONE) ? shift[32 * j + m] : 0.f;
+    sc[j] = (epilogue != EMC2_EPI_NONE) ? scale[16 * j + m] : 1.f;
+    sh[j] = (epilogue != EMC2_EPI_NONE) ? shift[16 * j + m] : 0.f;
   }
   uint16_t* otile = reinterpret_cast<uint16_t*>(my_tile);
   constexpr int OCH = COUT / 8;               // 16-byte pieces per output row
   constexpr int OPITCH = (OCH + 1) * 8;       // LDS row pitch in 16-bit units
-  constexpr int ORPI = 64 / OCH;              // rows one store instruction covers
-  static_assert(32 * (OCH + 1) <= (SMAX + 1) * ROW16, "a 32-row output tile fits the gather tile");
+  constexpr int OPI = 64 / OCH;               // rows one store instruction covers
+  constexpr int ONI = (16 + OPI - 1) / OPI;   // store instructions per 16-row tile
+  static_assert(16 * (OCH + 1) <= (SMAX + 1) * ROW16, "a 16-row output tile fits the gather tile");
   const int orow = lane / OCH, ochunk = lane % OCH;
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt) {
+  for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
+      for (int e = 0; e < 4; ++e) {
         float v = acc[mt][j][e];
         if (epilogue != EMC2_EPI_NONE) v = fmaf(v, sc[j], sh[j]);
         if (epilogue == EMC2_EPI_AFFINE_RELU) v = v > 0.f ? v : 0.f;
-        otile[(8 * (e / 4) + 4 * h + (e % 4)) * OPITCH + 32 * j + m] = MmaS<DT>::cvt(v);
+        otile[(4 * q + e) * OPITCH + 16 * j + m] = MmaS<DT>::cvt(v);
       }
     }
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int i = 0; i < 32 / ORPI; ++i) {
-      const int r = i * ORPI + orow;
-      const u32x4 piece = *reinterpret_cast<const u32x4*>(otile + r * OPITCH + ochunk * 8);
-      const int64_t o = wave_row0 + mt * 32 + r;
-      if (o < n_out) *reinterpret_cast<u32x4*>(out + o * COUT + ochunk * 8) = piece;
+    for (int i = 0; i < ONI; ++i) {
+      const int r = i * OPI + orow;
+      if (r < 16) {
+        const u32x4 piece = *reinterpret_cast<const u32x4*>(otile + r * OPITCH + ochunk * 8);
+        const int64_t o = wave_row0 + mt * 16 + r;
+        if (o < n_out) *reinterpret_cast<u32x4*>(out + o * COUT + ochunk * 8) = piece;
+      }
     }
     __builtin_amdgcn_wave_barrier();
   }
@@ -337,7 +347,7 @@ __global__ void __launch_bounds__(kSpanThreads, (SpanCfg<CIN>::MINW))
 k_spconv_span(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, const float* __restrict__ scale,
               const float* __restrict__ shift, int epilogue, const int32_t* __restrict__ nbr,
               const int32_t* __restrict__ d_n_out, int64_t capacity_out, uint16_t* __restrict__ out) {
-  constexpr int G16 = 3 * (CIN / 16) * (COUT / 32) * 64;
+  constexpr int G16 = 3 * (CIN / 32) * (COUT / 16) * 64;
   constexpr int SMAX = SpanCfg<CIN>::SMAX;
   constexpr int ROW16 = CIN / 8 + 1;
   static_assert(SMAX % (64 / (CIN / 8)) == 0 && SMAX >= 64, "the tile holds whole load instructions and at least the 64 rows of a pass");
@@ -372,7 +382,8 @@ void launch_span(const void* d_in, const void* d_wp, const float* d_scale, const
 
 }  // namespace
 
-// (32, 32) is instantiated and correct, but measured no faster than the per-tap kernel: not dispatched.
+// (32, 32) is instantiated and correct, but measured no faster than the per-tap kernels: not dispatched.
+// Weights: the packed layout of the register-direct kernel (emc2_spconv_direct_pack).
 bool emc2_spconv_span_supported(int cin, int cout) { return cin == 64 && cout == 64; }
 
 void emc2_spconv_span_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,

@@ -268,9 +268,11 @@ CONV_CASES = [
     (F16, 32, 64, (24, 24, 8), 1111, EPI_AFFINE),
     (F16, 64, 64, (16, 16, 8), 1500, EPI_AFFINE_RELU),
     (F16, 64, 64, (16, 16, 8), 1500, EPI_NONE),
+    (F16, 64, 32, (16, 16, 8), 1300, EPI_AFFINE),
     (F16, 64, 128, (16, 16, 8), 1027, EPI_AFFINE_RELU),
     (F16, 128, 128, (16, 16, 8), 777, EPI_AFFINE_RELU),
     (BF16, 64, 64, (16, 16, 8), 1500, EPI_AFFINE_RELU),
+    (BF16, 32, 32, (24, 24, 8), 2100, EPI_AFFINE_RELU),
     (BF16, 16, 32, (24, 24, 8), 999, EPI_AFFINE_RELU),
     (BF16, 4, 32, (24, 24, 8), 999, EPI_AFFINE_RELU),
 ]
