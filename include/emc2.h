@@ -6,7 +6,8 @@
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (HBM, on the context's device); h_* and plain
  *     struct/array arguments are HOST pointers.  The caller owns every input and output buffer;
- *     the context owns all scratch (voxel hash, cell-index slots, scan partials, status word),
+ *     the context owns all scratch (per-voxel point stash, cell-index slots, scan partials, status
+ *     word),
  *     allocated once in emc2_create.  No call below allocates or frees device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
  *     arguments synchronously, enqueue kernels on `stream` and return; they never block unless a
@@ -14,7 +15,7 @@
  *     so that downstream calls need no host round trip: launches are sized by `capacity`, kernels
  *     bound themselves by the device count.
  *   - Errors found on the host are returned at once.  Errors only the device can see (more voxels
- *     than `capacity`, hash table full) set a device status word; emc2_status_sync returns and
+ *     than `capacity`) set a device status word; emc2_status_sync returns and
  *     clears it.  After such an error the outputs of that call are truncated but in bounds.
  *   - Calls on one context must be issued on one stream at a time (they share its scratch).
  *   - Voxel order everywhere: ascending key ((b*Gz + z)*Gy + y)*Gx + x, i.e. lexicographic
@@ -32,7 +33,7 @@ extern "C" {
 typedef enum {
   EMC2_OK = 0,
   EMC2_ERR_INVALID_ARG = 1, /* null/mis-sized argument, size beyond what the context was made for */
-  EMC2_ERR_CAPACITY = 2,    /* more voxels than `capacity`, or the voxel hash filled up            */
+  EMC2_ERR_CAPACITY = 2,    /* more voxels than `capacity`                                         */
   EMC2_ERR_UNSUPPORTED = 3, /* channel count / dtype / key width the kernels do not cover          */
   EMC2_ERR_DEVICE = 4       /* a HIP runtime call failed; see emc2_last_error                      */
 } emc2_status;

@@ -42,19 +42,12 @@ __device__ __forceinline__ int4 decode_key(uint64_t key, int gx, int gy, int gz)
 
 // Voxel hash record (open addressing, linear probing): the key and its running sums share one
 // 32-byte sector so that a point touches a single sector for the CAS and its five atomic adds.
-struct __attribute__((aligned(32))) VoxRec {
-  unsigned long long key;  // EMPTY_KEY when free
-  float sum[4];            // x, y, z, intensity
-  uint32_t count;
-  uint32_t pad;
-};
-static_assert(sizeof(VoxRec) == 32, "VoxRec must be 32 bytes");
+// points a voxel's stash holds before further ones are added atomically (LiDAR voxels hold 1-2 points)
+#define EMC2_VOX_STASH 4
 
-#define EMC2_EMPTY_KEY 0xFFFFFFFFFFFFFFFFull
 
 // Device status bits (OR-ed by kernels, read by emc2_status_sync).
 #define EMC2_DEVFLAG_CAPACITY 1
-#define EMC2_DEVFLAG_HASH_FULL 2
 
 struct SlotMeta {
   int32_t grid[3];
@@ -70,9 +63,7 @@ struct emc2_ctx {
   int64_t slot_tiles;
   cellword_t** slots;       // host array [n_slots + 2] of device pointers
   SlotMeta* meta;           // host array [n_slots + 2]
-  VoxRec* table;            // [table_slots]
-  int64_t table_slots;      // power of two
-  int32_t* uslot;           // [max_voxels] hash slots of the distinct voxels, in claim order
+  float4* stash;            // [max_voxels][EMC2_VOX_STASH] points of each voxel, in arrival order
   uint32_t* partials;       // scan partial sums
   int64_t n_partials;
   int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count

@@ -32,12 +32,6 @@ bool emc2_grid_ok(const int32_t grid[3], int32_t n_batch, int64_t* n_cells) {
   return true;
 }
 
-static int64_t pow2_at_least(int64_t v) {
-  int64_t p = 1;
-  while (p < v) p <<= 1;
-  return p;
-}
-
 extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_points, int64_t max_voxels,
                                    int64_t max_cells, int32_t n_slots) {
   if (!out) return EMC2_ERR_INVALID_ARG;
@@ -71,11 +65,7 @@ extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_point
     TRY(hipMalloc((void**)&ctx->slots[s], bytes), "hipMalloc(index slot)");
     TRY(hipMemset(ctx->slots[s], 0, bytes), "hipMemset(index slot)");  // establishes the tile-flag invariant
   }
-  // the hash holds at most one entry per point and at most max_voxels useful ones; twice that many slots
-  ctx->table_slots = pow2_at_least(2 * (max_points < max_voxels ? max_points : max_voxels));
-  if (ctx->table_slots < 1024) ctx->table_slots = 1024;
-  TRY(hipMalloc((void**)&ctx->table, sizeof(VoxRec) * (size_t)ctx->table_slots), "hipMalloc(voxel hash)");
-  TRY(hipMalloc((void**)&ctx->uslot, sizeof(int32_t) * (size_t)max_voxels), "hipMalloc(uslot)");
+  TRY(hipMalloc((void**)&ctx->stash, sizeof(float4) * EMC2_VOX_STASH * (size_t)max_voxels), "hipMalloc(voxel stash)");
   ctx->n_partials = emc2_div_up(ctx->slot_words, EMC2_SCAN_TILE) + 1;
   TRY(hipMalloc((void**)&ctx->partials, sizeof(uint32_t) * (size_t)ctx->n_partials), "hipMalloc(partials)");
   TRY(hipMalloc((void**)&ctx->zero_row, 256), "hipMalloc(zero_row)");
@@ -102,8 +92,7 @@ extern "C" void emc2_destroy(emc2_ctx* ctx) {
     free(ctx->slots);
   }
   free(ctx->meta);
-  if (ctx->table) (void)hipFree(ctx->table);
-  if (ctx->uslot) (void)hipFree(ctx->uslot);
+  if (ctx->stash) (void)hipFree(ctx->stash);
   if (ctx->partials) (void)hipFree(ctx->partials);
   if (ctx->zero_row) (void)hipFree(ctx->zero_row);
   if (ctx->wpack) (void)hipFree(ctx->wpack);
@@ -123,10 +112,8 @@ extern "C" emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream) {
   st = emc2_check_hip(ctx, hipStreamSynchronize(s), "hipStreamSynchronize");
   if (st != EMC2_OK) return st;
   const int flags = ctx->pinned[0];
-  if (flags & (EMC2_DEVFLAG_CAPACITY | EMC2_DEVFLAG_HASH_FULL))
-    return emc2_fail(ctx, EMC2_ERR_CAPACITY, "device reported %s%s",
-                     (flags & EMC2_DEVFLAG_CAPACITY) ? "[more voxels than capacity]" : "",
-                     (flags & EMC2_DEVFLAG_HASH_FULL) ? "[voxel hash full]" : "");
+  if (flags & EMC2_DEVFLAG_CAPACITY)
+    return emc2_fail(ctx, EMC2_ERR_CAPACITY, "device reported [more voxels than capacity]");
   return EMC2_OK;
 }
 
