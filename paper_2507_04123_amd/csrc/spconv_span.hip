@@ -161,10 +161,15 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   }
   // gather of the interval [lo, hi] (rows past hi re-read row hi and are never referenced)
 #define EMC2_GATHER_SPAN(GI)                                                                               \
-  _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                      \
-    int32_t r_ = (GI).lo + i_ * RPI + srow;                                                                \
-    r_ = r_ < (GI).hi ? r_ : (GI).hi;                                                                      \
-    sreg[i_] = *(reinterpret_cast<const u32x4*>(in + (int64_t)r_ * CIN) + schunk);                         \
+  {                                                                                                        \
+    /* wave-uniform base (scalar registers) + a small per-lane byte offset */                              \
+    const char* base_ = reinterpret_cast<const char*>(in) + (int64_t)(GI).lo * (CIN * 2);                  \
+    const uint32_t last_ = (uint32_t)((GI).hi - (GI).lo);                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                    \
+      const uint32_t p_ = (uint32_t)(i_ * RPI + srow);                                                     \
+      const uint32_t off_ = (p_ < last_ ? p_ : last_) * (uint32_t)(CIN * 2) + (uint32_t)(schunk * 16);     \
+      sreg[i_] = *reinterpret_cast<const u32x4*>(base_ + off_);                                            \
+    }                                                                                                      \
   }
   // gather of exactly the rows one tap names: tile row p <- input row JROW[p] (absent entries re-read row 0)
 #define EMC2_GATHER_TAP(JROW)                                                                              \
@@ -215,23 +220,26 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     __builtin_amdgcn_wave_barrier();                                                                       \
     { const int32_t lrow_ = EMC2_LROW(2, C, GI); EMC2_TAP(2, lrow_, WB) }                                  \
   }
-  // prologue
+  // prologue.  The analyses of the groups (wave-uniform, ~80 scalar instructions each) are carried from
+  // iteration to iteration, one new analysis per group, always of entries loaded a whole group earlier.
   EMC2_IDX_LOAD(0, jq0)
   EMC2_IDX_LOAD(1, jq1)
   EMC2_W_LOAD(0)
   EMC2_W_STORE(0)
+  GroupInfo cur, nxt, aft;
   {
     EMC2_MASKED(c0, jq0)
-    const GroupInfo g0 = analyze<SMAX>(c0);
-    EMC2_GATHER_MAIN(g0, c0)
+    EMC2_MASKED(c1, jq1)
+    cur = analyze<SMAX>(c0);
+    nxt = analyze<SMAX>(c1);
+    aft = nxt;
+    EMC2_GATHER_MAIN(cur, c0)
     if constexpr (LATE) {
       // one interval ahead on the memory side: first pass of group 0 in the tile, next pass requested
       EMC2_TILE_WRITE()
-      EMC2_MASKED(c1, jq1)
-      const GroupInfo g1 = analyze<SMAX>(c1);
       EMC2_IDX_LOAD(2, jq2)
       EMC2_W_LOAD(1)
-      if (g0.span) { EMC2_GATHER_MAIN(g1, c1) } else { EMC2_GATHER_TAP(c0[1]) }
+      if (cur.span) { EMC2_GATHER_MAIN(nxt, c1) } else { EMC2_GATHER_TAP(c0[1]) }
     }
   }
   __syncthreads();
@@ -240,8 +248,6 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     const u32x4* wb = wl + (g & 1) * G16;
     EMC2_MASKED(c0, jq0)
     EMC2_MASKED(c1, jq1)
-    const GroupInfo cur = analyze<SMAX>(c0);
-    const GroupInfo nxt = analyze<SMAX>(c1);
     if constexpr (!LATE) {
       EMC2_TILE_WRITE()                       // rows of group g, requested during group g - 1
       // requests: entries of group g + 2, weights of group g + 1, and the rows of the next pass (group
@@ -256,15 +262,20 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
       }
       __builtin_amdgcn_wave_barrier();
       EMC2_W_STORE((g + 1) & 1)               // weights of group g + 1 -> the LDS buffer group g - 1 used
+      {
+        EMC2_MASKED(c2, jq2)                  // requested at the top of this group
+        cur = nxt;
+        nxt = analyze<SMAX>(c2);
+      }
     } else {
       // tile holds group g (first pass); registers hold the rows of the next pass; wq holds W(g + 1)
-      EMC2_MASKED(c2, jq2)
-      const GroupInfo aft = analyze<SMAX>(c2);
       // a group none of whose 192 entries is valid costs no LDS read and no matrix instruction
       if (((cur.valid[0] | cur.valid[1] | cur.valid[2]) != 0ull) || !cur.span) {
         EMC2_COMPUTE(c0, cur, nxt, c1, wb)
       }
       __builtin_amdgcn_wave_barrier();
+      EMC2_MASKED(c2, jq2)                    // requested at the end of the previous group
+      aft = analyze<SMAX>(c2);
       EMC2_W_STORE((g + 1) & 1)
       EMC2_TILE_WRITE()                       // first pass of group g + 1
       int32_t jn[3];
@@ -272,6 +283,8 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
       EMC2_W_LOAD(g + 2)
       // rows of the pass after that: second pass of group g + 1 if it runs in three passes, else group g + 2
       if (nxt.span) { EMC2_GATHER_MAIN(aft, c2) } else { EMC2_GATHER_TAP(c1[1]) }
+      cur = nxt;
+      nxt = aft;
 #pragma unroll
       for (int kx = 0; kx < 3; ++kx) {
         jq0[kx] = jq1[kx];

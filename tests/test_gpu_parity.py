@@ -86,7 +86,7 @@ def test_voxelize_edge_cases():
                     [4.0, 1, 1, 0.5]], np.float32)
     bad[-1, 0] = 4.0                                      # x = 4.0 -> t = 8.0 = G: dropped
     assert gpu_voxelize(ctx, bad, None, spec, 16)[5] == 0
-    # all points in one voxel (maximum contention on one hash record)
+    # all points in one voxel (maximum contention on one output row)
     st = gen.Stream(5)
     one = np.stack([st.uniform(4096, 1.0, 1.45), st.uniform(4096, 2.0, 2.45), st.uniform(4096, 3.0, 3.45),
                     st.uniform(4096)], axis=1).astype(np.float32)
@@ -111,6 +111,26 @@ def test_voxelize_edge_cases():
         gpu_voxelize(ctx, pts, batch, spec4, 100000)        # capacity > max_voxels
     with pytest.raises(B.Emc2Error):
         gpu_voxelize(ctx, pts, batch, VoxelSpec((0, 0, 0), (0.5, 0.5, 0.5), (64, 64, 64)), 100)   # > max_cells
+    ctx.close()
+
+
+def test_voxelize_crowded_voxels():
+    """Many points per voxel: a voxel's first few points are parked in its stash, the rest are added
+    atomically; counts are exact whatever the mix (1, exactly the stash depth, one more, hundreds)."""
+    spec = VoxelSpec((0.0, 0.0, 0.0), (1.0, 1.0, 1.0), (6, 5, 3))
+    st = gen.Stream(99, 7)
+    per_cell = {(0, 0, 0): 1, (1, 0, 0): 2, (2, 0, 0): 3, (3, 0, 0): 4, (4, 0, 0): 5, (5, 0, 0): 6,
+                (0, 1, 0): 9, (1, 2, 1): 64, (2, 3, 2): 700, (5, 4, 2): 3000}
+    rows = []
+    for (cx, cy, cz), n in per_cell.items():
+        q = st.uniform(4 * n, 0.05, 0.95).astype(np.float32).reshape(n, 4)
+        q[:, 0] += cx; q[:, 1] += cy; q[:, 2] += cz
+        rows.append(q)
+    pts = np.concatenate(rows)[st.permutation(sum(per_cell.values()))]
+    ctx = B.Context(len(pts), 64, cells_of(spec.grid, 1), n_slots=1)
+    for _ in range(2):                                             # twice: the stash is reused between calls
+        nv = check_voxelize(ctx, pts, None, spec, 64)[5]
+        assert nv == len(per_cell)
     ctx.close()
 
 
