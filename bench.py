@@ -108,6 +108,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tight-capacity", action="store_true",
                     help="size per-level capacities from a calibration pass (x1.25) instead of the safe bounds")
+    ap.add_argument("--serial", action="store_true",
+                    help="issue every call on one stream (default: map building on a second stream, overlapping the convs)")
+    ap.add_argument("--frames-in-flight", type=int, default=2, choices=[1, 2],
+                    help="2: two contexts alternate frames, so the maps of frame f+1 are built while the convs of "
+                         "frame f run (throughput mode; each step is still one whole frame); 1: one frame at a time")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -169,9 +174,30 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    depth = 1 if args.serial else args.frames_in_flight
+    ctx2 = runner2 = None
+    if depth == 2:
+        ctx2, runner2 = make(caps)
+        runner2.run(pts, batch)
+        ctx2.status_sync()
+    torch.cuda.synchronize()
+    inputs_ready = torch.cuda.Event()
+    inputs_ready.record()             # the points are resident and complete from here on
+    torch.cuda.synchronize()
+    step_no = [0]
+
+    def step(p, b, tm=None):
+        if args.serial:
+            return runner.run(p, b, tm)
+        if depth == 1:
+            return runner.run_overlapped(p, b, tm)
+        r = runner if step_no[0] % 2 == 0 else runner2
+        step_no[0] += 1
+        return r.run_overlapped(p, b, tm, inputs_ready=inputs_ready)
+
     timer = EventTimer(torch)
     for _ in range(args.warmup):
-        runner.run(pts, batch)
+        step(pts, batch)
     torch.cuda.synchronize()
 
     # Calibration pass (outside the timed region): every library call bracketed by events, to find the
@@ -207,10 +233,12 @@ def main() -> int:
     t0 = time.perf_counter()
     for i in range(args.steps):
         timer.enabled = (i % 4 == 0)
-        runner.run(pts, batch, timer)
+        step(pts, batch, timer)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ctx.status_sync()
+    if ctx2 is not None:
+        ctx2.status_sync()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     frames_per_s = cfg.n_frames * args.steps / (t1 - t0)
 
@@ -237,6 +265,7 @@ def main() -> int:
         "value": frames_per_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
+        "streams": 1 if args.serial else 2, "frames_in_flight": depth,
         "config": {"workload": f"config {cfg.index} ({cfg.name}): {cfg.n_points} points x {cfg.n_frames} frame(s), "
                                f"grid {br.spec.grid}, {len(br.layers)} sparse convs", "capacities": caps,
                    "voxels_per_level": n_vox},
@@ -249,6 +278,8 @@ def main() -> int:
                         for l, p, m in zip(br.layers, layer_pairs, conv_ms)],
     }
     ctx.close()
+    if ctx2 is not None:
+        ctx2.close()
     if not args.no_cpu_baseline:
         import oracle
         threads = min(oracle.max_threads(), 16)

@@ -17,7 +17,11 @@
  *   - Errors found on the host are returned at once.  Errors only the device can see (more voxels
  *     than `capacity`) set a device status word; emc2_status_sync returns and
  *     clears it.  After such an error the outputs of that call are truncated but in bounds.
- *   - Calls on one context must be issued on one stream at a time (they share its scratch).
+ *   - emc2_voxelize, emc2_build_kmap and emc2_spconv with EMC2_W_PLAIN weights on an MFMA shape share
+ *     the context's scratch: issue them on one stream at a time.  emc2_spconv with packed (or non-MFMA)
+ *     weights, emc2_pack_weights into caller memory and emc2_project_gather touch no mutable context
+ *     state and may run on other streams concurrently, ordered by the caller's events (a conv must
+ *     wait for the call that wrote the map and features it reads).
  *   - Voxel order everywhere: ascending key ((b*Gz + z)*Gy + y)*Gx + x, i.e. lexicographic
  *     (b, z, y, x).  Coordinates are int32 quadruples (b, z, y, x).
  */

@@ -122,6 +122,83 @@ class BranchRunner:
             if layer.kind == STRIDED:
                 lvl += 1
             self.acts.append(torch.empty((self.levels[lvl].cap, layer.cout), dtype=_TD[dtype], device=device))
+        # Second stream for voxelization and kernel maps.  They share the context's scratch and stay ordered
+        # among themselves; the convolutions (packed weights: no context scratch) run on the caller's stream
+        # and wait, per layer, only for the map they read.  Both streams keep the default priority.
+        self.map_stream = torch.cuda.Stream(device=device)
+        self.ev_feats = torch.cuda.Event()
+        self.ev_done = None           # recorded on the caller's stream at the end of the previous overlapped run
+        self.ev_subm = [torch.cuda.Event() for _ in self.levels]
+        self.ev_down = [torch.cuda.Event() for _ in self.levels]
+        self.can_overlap = all(lay == B.W_PACKED or not ctx.uses_mfma(dtype, l.cin, l.cout)
+                               for (_, lay), l in zip(self.wdev, branch.layers))
+
+    def run_overlapped(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None,
+                       inputs_ready: Optional["torch.cuda.Event"] = None) -> torch.Tensor:
+        """Same results as run(); map building is issued on a second stream and overlaps the convolutions.
+        `timer` brackets the conv calls only (they are the ones on the caller's stream).
+
+        The second stream waits for `inputs_ready` if given, else for everything issued so far on the caller's
+        stream.  Passing an event lets two runners (two contexts) alternate frames: the maps of frame f+1 are
+        then built while the convolutions of frame f still run."""
+        if not self.can_overlap:
+            return self.run(points, batch, timer)
+        ctx, br = self.ctx, self.branch
+        tm = timer if timer is not None else _no_timer
+        main = torch.cuda.current_stream()
+        ms = self.map_stream
+        nb = br.spec.n_batch
+        if inputs_ready is None:
+            ms.wait_stream(main)      # inputs, and the previous frame's readers of the buffers rewritten below
+        else:
+            ms.wait_event(inputs_ready)
+            if self.ev_done is not None:
+                ms.wait_event(self.ev_done)   # this runner's previous frame: its convs read what is rewritten below
+        with torch.cuda.stream(ms):
+            l0 = self.levels[0]
+            ctx.voxelize(points, batch, br.spec, l0.cap, l0.coords, self.feats32, self.counts, l0.n,
+                         feats_lp=self.feats_lp, index_slot=l0.slot)
+            self.ev_feats.record(ms)
+            lvl = 0
+            built = [False] * len(self.levels)
+            for layer in br.layers:
+                if layer.kind == STRIDED:
+                    src, dst = self.levels[lvl], self.levels[lvl + 1]
+                    ctx.build_kmap(B.STRIDED, src.coords, src.n, src.cap, src.grid, nb, dst.cap, dst.down_nbr, dst.n,
+                                   out_coords=dst.coords, in_slot=src.slot, out_slot=dst.slot)
+                    lvl += 1
+                    self.ev_down[lvl].record(ms)
+                elif not built[lvl]:
+                    lv = self.levels[lvl]
+                    ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n, in_slot=lv.slot)
+                    built[lvl] = True
+                    self.ev_subm[lvl].record(ms)
+        main.wait_event(self.ev_feats)
+        x = self.feats32 if self.dtype == F32 else self.feats_lp
+        lvl = 0
+        for li, layer in enumerate(br.layers):
+            p = self.params[li]
+            has_epi = layer.epilogue != EPI_NONE
+            if layer.kind == STRIDED:
+                lvl += 1
+                lv = self.levels[lvl]
+                main.wait_event(self.ev_down[lvl])
+                nbr = lv.down_nbr
+            else:
+                lv = self.levels[lvl]
+                main.wait_event(self.ev_subm[lvl])
+                nbr = lv.subm_nbr
+            y = self.acts[li]
+            with tm(("conv", li)):
+                ctx.spconv(self.dtype, x, self.wdev[li][0], p["scale"] if has_epi else None,
+                           p["shift"] if has_epi else None, layer.epilogue, nbr, lv.n, lv.cap, y,
+                           w_layout=self.wdev[li][1], map_hint=layer.kind)
+            x = y
+        main.wait_stream(ms)          # everything of this frame is now ordered before later work on the caller's stream
+        if self.ev_done is None:
+            self.ev_done = torch.cuda.Event()
+        self.ev_done.record(main)
+        return x
 
     def run(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> torch.Tensor:
         """One pass of the branch.  `timer`, if given, is called as timer(tag) and must return a context

@@ -516,3 +516,66 @@ def test_config4_and_5_reduced_end_to_end():
         pts, batch = pts[::4].copy(), batch[::4].copy()
         for br in cfg.branches:
             run_config_branch(cfg, br, pts, batch if cfg.n_frames > 1 else None, True)
+
+
+@pytest.mark.parametrize("cfg_index", [2, 5])
+def test_two_stream_run_matches_single_stream(cfg_index):
+    """Map building on a second stream (overlapping the convolutions) must change nothing: coordinates, counts
+    and kernel maps bit for bit, activations up to the voxel means' atomic summation order.  Alternating the two
+    ways of running over several frames also exercises the cross-frame ordering of the reused buffers."""
+    cfg = get_config(cfg_index)
+    br = cfg.branches[0]
+    pts_np, batch_np = gen.make_frames(cfg)
+    pts = dev(pts_np)
+    batch = dev(batch_np) if cfg.n_frames > 1 else None
+    seed = gen.frame_seed(cfg.index, 0)
+    caps = default_capacities(br, len(pts_np))
+    ctx = B.Context(len(pts_np), max(caps), cells_of(br.spec.grid, br.spec.n_batch), n_slots=len(caps))
+    runner = BranchRunner(ctx, br, cfg.dtype, len(pts_np), device_params(br.layers, seed, cfg.dtype), capacities=caps)
+    assert runner.can_overlap
+
+    def snapshot(out):
+        torch.cuda.synchronize()
+        ctx.status_sync()
+        ns = [int(lv.n.item()) for lv in runner.levels]
+        maps = []
+        for li in range(len(br.layers)):
+            nbr, lv = runner.layer_map(li)
+            maps.append(nbr[:, :int(lv.n.item())].clone())
+        return ns, [lv.coords[:n].clone() for lv, n in zip(runner.levels, ns)], maps, out[:ns[-1]].float().clone()
+
+    ref = snapshot(runner.run(pts, batch))
+    for it in range(4):
+        print(f"two-stream run cfg{cfg_index} iteration {it}", flush=True)
+        got = snapshot(runner.run_overlapped(pts, batch) if it % 2 == 0 else runner.run(pts, batch))
+        assert got[0] == ref[0]
+        for a, b in zip(got[1], ref[1]):
+            assert torch.equal(a, b)
+        for a, b in zip(got[2], ref[2]):
+            assert torch.equal(a, b)
+        assert_features_close(got[3].cpu().numpy(), ref[3].cpu().numpy(), 2e-2, "two-stream activations")
+
+    # two runners (two contexts) alternating frames, the maps of one frame built under the convs of the previous
+    ctx_b = B.Context(len(pts_np), max(caps), cells_of(br.spec.grid, br.spec.n_batch), n_slots=len(caps))
+    runner_b = BranchRunner(ctx_b, br, cfg.dtype, len(pts_np), device_params(br.layers, seed, cfg.dtype), capacities=caps)
+    torch.cuda.synchronize()
+    ready = torch.cuda.Event()
+    ready.record()
+    outs = []
+    for it in range(6):
+        r = runner if it % 2 == 0 else runner_b
+        outs.append((r, r.run_overlapped(pts, batch, inputs_ready=ready)))
+    torch.cuda.synchronize()
+    ctx.status_sync()
+    ctx_b.status_sync()
+    for r, out in outs[-2:]:
+        ns = [int(lv.n.item()) for lv in r.levels]
+        assert ns == ref[0]
+        for lv, n, c in zip(r.levels, ns, ref[1]):
+            assert torch.equal(lv.coords[:n], c)
+        for li in range(len(br.layers)):
+            nbr, lv = r.layer_map(li)
+            assert torch.equal(nbr[:, :int(lv.n.item())], ref[2][li])
+        assert_features_close(out[:ns[-1]].float().cpu().numpy(), ref[3].cpu().numpy(), 2e-2, "alternating runners")
+    ctx_b.close()
+    ctx.close()
