@@ -111,8 +111,8 @@ def main() -> int:
     ap.add_argument("--serial", action="store_true",
                     help="issue every call on one stream (default: map building on a second stream, overlapping the convs)")
     ap.add_argument("--conv-streams", type=int, default=2, choices=[1, 2],
-                    help="with two frames in flight: 2 gives each context its own conv stream as well")
-    ap.add_argument("--frames-in-flight", type=int, default=2, choices=[1, 2],
+                    help="with several frames in flight: 2 gives each context its own conv stream as well")
+    ap.add_argument("--frames-in-flight", type=int, default=2, choices=[1, 2, 3, 4],
                     help="2: two contexts alternate frames, so the maps of frame f+1 are built while the convs of "
                          "frame f run (throughput mode; each step is still one whole frame); 1: one frame at a time")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
@@ -177,30 +177,31 @@ def main() -> int:
         del src, dst
 
     depth = 1 if args.serial else args.frames_in_flight
-    ctx2 = runner2 = None
-    if depth == 2:
-        ctx2, runner2 = make(caps)
-        runner2.run(pts, batch)
-        ctx2.status_sync()
+    ring = [(ctx, runner)]            # one context (scratch, buffers, streams) per frame in flight
+    for _ in range(depth - 1):
+        c_, r_ = make(caps)
+        r_.run(pts, batch)
+        c_.status_sync()
+        ring.append((c_, r_))
     torch.cuda.synchronize()
     inputs_ready = torch.cuda.Event()
     inputs_ready.record()             # the points are resident and complete from here on
     torch.cuda.synchronize()
     step_no = [0]
-    conv_streams = [torch.cuda.Stream(), torch.cuda.Stream()] if (depth == 2 and args.conv_streams == 2) else None
+    conv_streams = [torch.cuda.Stream() for _ in ring] if (depth >= 2 and args.conv_streams == 2) else None
 
     def step(p, b, tm=None):
         if args.serial:
             return runner.run(p, b, tm)
         if depth == 1:
             return runner.run_overlapped(p, b, tm)
-        k = step_no[0] % 2
+        k = step_no[0] % depth
         step_no[0] += 1
-        if args.conv_streams == 2:
-            # each context also gets a conv stream of its own: the convs of two frames share the machine
+        if conv_streams is not None:
+            # each context also gets a conv stream of its own: the convs of consecutive frames share the machine
             with torch.cuda.stream(conv_streams[k]):
-                return (runner, runner2)[k].run_overlapped(p, b, tm, inputs_ready=inputs_ready)
-        return (runner, runner2)[k].run_overlapped(p, b, tm, inputs_ready=inputs_ready)
+                return ring[k][1].run_overlapped(p, b, tm, inputs_ready=inputs_ready)
+        return ring[k][1].run_overlapped(p, b, tm, inputs_ready=inputs_ready)
 
     timer = EventTimer(torch)
     for _ in range(args.warmup):
@@ -243,9 +244,8 @@ def main() -> int:
         step(pts, batch, timer)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ctx.status_sync()
-    if ctx2 is not None:
-        ctx2.status_sync()
+    for c_, _ in ring:
+        c_.status_sync()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     frames_per_s = cfg.n_frames * args.steps / (t1 - t0)
 
@@ -295,9 +295,8 @@ def main() -> int:
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m}
                         for l, p, m in zip(br.layers, layer_pairs, conv_ms)],
     }
-    ctx.close()
-    if ctx2 is not None:
-        ctx2.close()
+    for c_, _ in ring:
+        c_.close()
     if not args.no_cpu_baseline:
         import oracle
         threads = min(oracle.max_threads(), 16)
