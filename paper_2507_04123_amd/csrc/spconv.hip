@@ -44,9 +44,12 @@ __global__ void __launch_bounds__(256) k_spconv_alu(const T* __restrict__ in, co
 }
 
 // Small-channel kernel (Cin in {4, 16}, Cout in {16, 32}: the input layers that sit below the matrix-core
-// tile sizes).  One thread owns one output row and all of its Cout accumulators; the 27 taps run in
-// lockstep across the wave, so a tap's weights are LDS broadcasts and a tap nobody in the wave has is
-// skipped.  Kernel-map entries are fetched one tap ahead with an unconditional load.
+// tile sizes).  One thread owns one output row and all of its Cout accumulators; a tap's weights are LDS
+// broadcasts and a tap nobody in the wave has is skipped.  These layers have few rows (one wave per 64 of
+// them, a handful of waves per CU), so latency, not bandwidth, is what they can lose time to: all 27
+// kernel-map entries of a row are requested at once, and the feature rows of a whole batch of taps (27 at
+// Cin = 4, 9 at Cin = 16) are requested together, unconditionally (absent entries re-read row 0), before
+// the first of them is used -- two memory round trips per batch instead of two per tap.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 
@@ -58,41 +61,61 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
                                                       T* __restrict__ out) {
   __shared__ float wl[27 * CIN * COUT];
   for (int i = threadIdx.x; i < 27 * CIN * COUT; i += 256) wl[i] = to_f32(w[i]);
-  __syncthreads();
   int64_t n = *d_n_out;
   if (n > capacity_out) n = capacity_out;
   const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const bool live = o < n;
   const int32_t* nrow = nbr + (live ? o : 0);
   const int32_t dead = live ? 0 : -1;
+  constexpr int ROW_BYTES = CIN * (int)sizeof(T);
+  static_assert(ROW_BYTES == 8 || ROW_BYTES % 16 == 0, "feature rows are read with 8- or 16-byte loads");
+  constexpr int RW = ROW_BYTES / 4;               // 32-bit words per feature row
+  constexpr int TB = ROW_BYTES <= 8 ? 27 : 9;     // taps whose rows are in flight together
+  int32_t j[27];
+#pragma unroll
+  for (int k = 0; k < 27; ++k) j[k] = nrow[(int64_t)k * capacity_out];
   float acc[COUT];
 #pragma unroll
   for (int d = 0; d < COUT; ++d) acc[d] = 0.f;
-  constexpr int ROW_BYTES = CIN * (int)sizeof(T);
-  static_assert(ROW_BYTES % 8 == 0, "feature rows are read with 8- or 16-byte loads");
-  int32_t jn = nrow[0];
-  for (int k = 0; k < 27; ++k) {
-    const int32_t j = jn | dead;
-    jn = nrow[(int64_t)(k + 1 < 27 ? k + 1 : 26) * capacity_out];
-    if (__ballot(j >= 0) == 0ull) continue;  // wave-uniform
-    if (j >= 0) {
-      alignas(16) T xr[CIN];
-      const char* src = reinterpret_cast<const char*>(in + (int64_t)j * CIN);
-      if constexpr (ROW_BYTES % 16 == 0) {
+  __syncthreads();   // weights in LDS
 #pragma unroll
-        for (int q = 0; q < ROW_BYTES / 16; ++q)
-          reinterpret_cast<u32x4_t*>(xr)[q] = reinterpret_cast<const u32x4_t*>(src)[q];
+  for (int k0 = 0; k0 < 27; k0 += TB) {
+    uint32_t xr[TB][RW];
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+      const int32_t jj = j[k0 + t] | dead;
+      const char* src = reinterpret_cast<const char*>(in + (int64_t)(jj >= 0 ? jj : 0) * CIN);
+      if constexpr (ROW_BYTES == 8) {
+        const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src);
+        xr[t][0] = v.x; xr[t][1] = v.y;
       } else {
 #pragma unroll
-        for (int q = 0; q < ROW_BYTES / 8; ++q)
-          reinterpret_cast<u32x2_t*>(xr)[q] = reinterpret_cast<const u32x2_t*>(src)[q];
+        for (int q = 0; q < ROW_BYTES / 16; ++q) {
+          const u32x4_t v = reinterpret_cast<const u32x4_t*>(src)[q];
+          xr[t][4 * q] = v.x; xr[t][4 * q + 1] = v.y; xr[t][4 * q + 2] = v.z; xr[t][4 * q + 3] = v.w;
+        }
       }
-      const float* wk = wl + k * CIN * COUT;
+    }
 #pragma unroll
-      for (int c = 0; c < CIN; ++c) {
-        const float xv = to_f32(xr[c]);
+    for (int t = 0; t < TB; ++t) {
+      const int k = k0 + t;
+      const bool have = (j[k] | dead) >= 0;
+      if (__ballot(have) == 0ull) continue;  // wave-uniform
+      if (have) {
+        const float* wk = wl + k * CIN * COUT;
 #pragma unroll
-        for (int d = 0; d < COUT; ++d) acc[d] = fmaf(xv, wk[c * COUT + d], acc[d]);
+        for (int c = 0; c < CIN; ++c) {
+          T xe;
+          if constexpr (sizeof(T) == 2) {
+            const uint16_t bits = (uint16_t)(xr[t][c / 2] >> (16 * (c % 2)));
+            xe = __builtin_bit_cast(T, bits);
+          } else {
+            xe = __builtin_bit_cast(T, xr[t][c]);
+          }
+          const float xv = to_f32(xe);
+#pragma unroll
+          for (int d = 0; d < COUT; ++d) acc[d] = fmaf(xv, wk[c * COUT + d], acc[d]);
+        }
       }
     }
   }
