@@ -275,6 +275,57 @@ def main() -> int:
                           "avg_launch_ms": excl_ms / max(len(dom_layers), 1),
                           "note": "calibration pass outside the timed region, kernel alone on the GPU"}
 
+    # Memory-bound stages: algorithmic bytes (what the method itself must move) over the calibration pass's
+    # stage time, against the published HBM peak.  voxelize: 16 B per point read, 36 B per voxel written;
+    # kernel maps: 16 B of coordinates read and 27 x 4 B of map written per output voxel (+ 16 B of coordinates
+    # written per stride-2 output, 16 B read per stride-2 input).
+    stage_bytes = {"voxelize": n_points * 16.0 + n_vox[0] * 36.0, "kmap_subm": 0.0, "kmap_strided": 0.0}
+    lvl_ = 0
+    seen_subm = set()
+    for layer in br.layers:
+        if layer.kind == STRIDED:
+            stage_bytes["kmap_strided"] += n_vox[lvl_] * 16.0 + n_vox[lvl_ + 1] * (16.0 + 16.0 + 108.0)
+            lvl_ += 1
+        elif lvl_ not in seen_subm:
+            seen_subm.add(lvl_)
+            stage_bytes["kmap_subm"] += n_vox[lvl_] * (16.0 + 108.0)
+    stage_hbm = {}
+    for k_, b_ in stage_bytes.items():
+        if stage_ms.get(k_):
+            gbs = b_ / (stage_ms[k_] * 1e-3) / 1e9
+            stage_hbm[k_] = {"algorithmic_MB": b_ / 1e6, "ms": stage_ms[k_], "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+
+    # the fifth call of the boundary, on its own workload (config 3: every point of the frame samples a
+    # 375 x 1242 x 64 fp16 feature map): 16 B + 4 corners x 128 B + 128 B + 1 B per point
+    pg = None
+    try:
+        cfg3 = get_config(3)
+        cam = cfg3.camera
+        pts3_np, _ = gen.make_frames(cfg3)
+        pts3 = torch.from_numpy(pts3_np).cuda()
+        img = torch.from_numpy(gen.make_image(cam.height, cam.width, cam.channels, gen.frame_seed(3, 0))).cuda()
+        pm = gen.make_camera(gen.frame_seed(3, 0))
+        g_out = torch.empty((len(pts3_np), cam.channels), dtype=torch.float16, device="cuda")
+        g_valid = torch.empty((len(pts3_np),), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            ctx.project_gather(pts3, pm, img, g_out, g_valid)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(20):
+            ctx.project_gather(pts3, pm, img, g_out, g_valid)
+        e1.record()
+        torch.cuda.synchronize()
+        pg_ms = e0.elapsed_time(e1) / 20.0
+        pg_bytes = len(pts3_np) * (16.0 + 4 * 2.0 * cam.channels + 2.0 * cam.channels + 1.0)
+        pg = {"workload": f"config 3: {len(pts3_np)} points, image {cam.height}x{cam.width}x{cam.channels} f16",
+              "ms": pg_ms, "algorithmic_MB": pg_bytes / 1e6, "GB/s": pg_bytes / (pg_ms * 1e-3) / 1e9,
+              "frac_of_hbm_peak": pg_bytes / (pg_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+              "valid_points": int(g_valid.sum().item())}
+        del img, g_out, g_valid, pts3
+    except Exception as exc:  # the side measurement must never take the headline number down with it
+        pg = {"error": repr(exc)}
+
     total_flops = sum(layer_flops)
     vox_ms = stage_ms.get("voxelize", 0.0)
     out = {
@@ -292,8 +343,13 @@ def main() -> int:
         "voxelize_mpts_per_s": (n_points / (vox_ms * 1e-3) / 1e6) if vox_ms > 0 else None,
         "conv_useful_gflop_per_frame": total_flops / 1e9,
         "conv_useful_tflops": total_flops / (stage_ms.get("conv", 0.0) * 1e-3) / 1e12 if stage_ms.get("conv") else None,
-        "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m}
-                        for l, p, m in zip(br.layers, layer_pairs, conv_ms)],
+        "memory_bound_stages": stage_hbm,
+        "project_gather": pg,
+        "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
+                         "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),
+                         "useful_tflops": (f / (m * 1e-3) / 1e12) if m > 0 else None,
+                         "frac_of_mfma_peak": (f / (m * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS) if m > 0 else None}
+                        for l, p, m, f in zip(br.layers, layer_pairs, conv_ms, layer_flops)],
     }
     for c_, _ in ring:
         c_.close()
