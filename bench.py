@@ -115,6 +115,7 @@ def main() -> int:
     ap.add_argument("--frames-in-flight", type=int, default=2, choices=[1, 2, 3, 4],
                     help="2: two contexts alternate frames, so the maps of frame f+1 are built while the convs of "
                          "frame f run (throughput mode; each step is still one whole frame); 1: one frame at a time")
+    ap.add_argument("--no-scaling-sweep", action="store_true", help="skip the voxelizer batch-size sweep")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -326,6 +327,43 @@ def main() -> int:
     except Exception as exc:  # the side measurement must never take the headline number down with it
         pg = {"error": repr(exc)}
 
+    # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
+    # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
+    vox_scaling = []
+    if args.config == 2 and not args.no_scaling_sweep:
+        try:
+            from paper_2507_04123_amd.configs import VoxelSpec
+            for nb_ in (1, 8, 32):
+                pts_b = pts.repeat(nb_, 1).contiguous()
+                bid = torch.arange(nb_, dtype=torch.int32, device="cuda").repeat_interleave(n_points).contiguous()
+                sp_ = VoxelSpec(br.spec.lo, br.spec.vs, br.spec.grid, n_batch=nb_)
+                cap_ = n_points * nb_
+                cx_ = B.Context(cap_, cap_, cells_of(sp_.grid, nb_), n_slots=1)
+                co_ = torch.empty((cap_, 4), dtype=torch.int32, device="cuda")
+                fe_ = torch.empty((cap_, 4), dtype=torch.float32, device="cuda")
+                cn_ = torch.empty((cap_,), dtype=torch.int32, device="cuda")
+                nn_ = torch.zeros(1, dtype=torch.int32, device="cuda")
+                for _ in range(2):
+                    cx_.voxelize(pts_b, bid, sp_, cap_, co_, fe_, cn_, nn_, index_slot=0)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(5):
+                    cx_.voxelize(pts_b, bid, sp_, cap_, co_, fe_, cn_, nn_, index_slot=0)
+                e1.record()
+                torch.cuda.synchronize()
+                cx_.status_sync()
+                ms_ = e0.elapsed_time(e1) / 5.0
+                nv_ = int(nn_.item())
+                by_ = cap_ * 20.0 + nv_ * 36.0   # 16 B point + 4 B batch id read; 36 B per voxel written
+                vox_scaling.append({"frames": nb_, "points": cap_, "voxels": nv_, "ms": ms_,
+                                    "Mpts/s": cap_ / (ms_ * 1e-3) / 1e6, "GB/s": by_ / (ms_ * 1e-3) / 1e9,
+                                    "frac_of_hbm_peak": by_ / (ms_ * 1e-3) / 1e9 / PEAK_HBM_GBS})
+                cx_.close()
+                del pts_b, bid, co_, fe_, cn_, nn_
+        except Exception as exc:
+            vox_scaling.append({"error": repr(exc)})
+
     total_flops = sum(layer_flops)
     vox_ms = stage_ms.get("voxelize", 0.0)
     out = {
@@ -345,6 +383,7 @@ def main() -> int:
         "conv_useful_tflops": total_flops / (stage_ms.get("conv", 0.0) * 1e-3) / 1e12 if stage_ms.get("conv") else None,
         "memory_bound_stages": stage_hbm,
         "project_gather": pg,
+        "voxelize_scaling": vox_scaling,
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
                          "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),
                          "useful_tflops": (f / (m * 1e-3) / 1e12) if m > 0 else None,
