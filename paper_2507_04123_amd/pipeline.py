@@ -134,7 +134,7 @@ class BranchRunner:
                                for (_, lay), l in zip(self.wdev, branch.layers))
 
     def run_overlapped(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None,
-                       inputs_ready: Optional["torch.cuda.Event"] = None) -> torch.Tensor:
+                       inputs_ready: Optional["torch.cuda.Event"] = None, _capturing: bool = False) -> torch.Tensor:
         """Same results as run(); map building is issued on a second stream and overlaps the convolutions.
         `timer` brackets the conv calls only (they are the ones on the caller's stream).
 
@@ -195,10 +195,26 @@ class BranchRunner:
                            w_layout=self.wdev[li][1], map_hint=layer.kind)
             x = y
         main.wait_stream(ms)          # everything of this frame is now ordered before later work on the caller's stream
+        if _capturing:
+            return x
         if self.ev_done is None:
             self.ev_done = torch.cuda.Event()
         self.ev_done.record(main)
         return x
+
+    def capture(self, points: torch.Tensor, batch: Optional[torch.Tensor], overlapped: bool = True) -> "torch.cuda.CUDAGraph":
+        """Record one whole frame (both streams, with their event dependencies) into a HIP graph: a frame is
+        ~50 small launches, and issuing them from the host one by one costs about as long as the GPU needs to run
+        them.  The graph reads `points` / `batch` and writes this runner's buffers, as run() does; replay it with
+        graph.replay() on any stream.  The library records no memset node (every clear is a kernel)."""
+        side = torch.cuda.Stream(device=points.device)
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            out = self.run_overlapped(points, batch, _capturing=True) if (overlapped and self.can_overlap) else self.run(points, batch)
+        torch.cuda.current_stream().wait_stream(side)
+        self.graph, self.graph_out = graph, out
+        return graph
 
     def run(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> torch.Tensor:
         """One pass of the branch.  `timer`, if given, is called as timer(tag) and must return a context

@@ -579,3 +579,53 @@ def test_two_stream_run_matches_single_stream(cfg_index):
         assert_features_close(out[:ns[-1]].float().cpu().numpy(), ref[3].cpu().numpy(), 2e-2, "alternating runners")
     ctx_b.close()
     ctx.close()
+
+
+def test_graph_replay_matches_eager_runs():
+    """A whole frame recorded into a HIP graph: every replay -- with eager runs and synchronisations in
+    between, and after the input buffer has been refilled with another frame -- gives the eager result."""
+    cfg = get_config(2)
+    br = cfg.branches[0]
+    pts_np, _ = gen.make_frames(cfg)
+    pts_b_np = pts_np[gen.Stream(4321).permutation(len(pts_np))][: len(pts_np)].copy()
+    pts_b_np[:, 0] += 0.37                                        # a different frame: other voxels, other maps
+    pts = dev(pts_np)
+    seed = gen.frame_seed(cfg.index, 0)
+    caps = default_capacities(br, len(pts_np))
+    ctx = B.Context(len(pts_np), max(caps), cells_of(br.spec.grid, 1), n_slots=len(caps))
+    runner = BranchRunner(ctx, br, cfg.dtype, len(pts_np), device_params(br.layers, seed, cfg.dtype), capacities=caps)
+
+    def snapshot(out):
+        torch.cuda.synchronize()
+        ctx.status_sync()
+        ns = [int(lv.n.item()) for lv in runner.levels]
+        maps = []
+        for li in range(len(br.layers)):
+            nbr, lv = runner.layer_map(li)
+            maps.append(nbr[:, :int(lv.n.item())].clone())
+        return ns, [lv.coords[:n].clone() for lv, n in zip(runner.levels, ns)], maps, out[:ns[-1]].float().clone()
+
+    def same(a, b, what):
+        assert a[0] == b[0], what
+        for x, y in zip(a[1], b[1]):
+            assert torch.equal(x, y), what
+        for x, y in zip(a[2], b[2]):
+            assert torch.equal(x, y), what
+        assert_features_close(a[3].cpu().numpy(), b[3].cpu().numpy(), 2e-2, what)
+
+    frame = pts.clone()                                           # the buffer the graph reads
+    ref_a = snapshot(runner.run(frame, None))
+    frame.copy_(dev(pts_b_np))
+    ref_b = snapshot(runner.run(frame, None))
+    assert ref_a[0] != ref_b[0]
+    frame.copy_(pts)
+    graph = runner.capture(frame, None)
+    torch.cuda.synchronize()
+    for it in range(5):
+        print(f"graph replay {it}", flush=True)
+        use_b = it % 2 == 1
+        frame.copy_(dev(pts_b_np) if use_b else pts)
+        graph.replay()
+        same(snapshot(runner.graph_out), ref_b if use_b else ref_a, f"replay {it}")
+        same(snapshot(runner.run_overlapped(frame, None)), ref_b if use_b else ref_a, f"eager after replay {it}")
+    ctx.close()
