@@ -112,9 +112,11 @@ def main() -> int:
                     help="issue every call on one stream (default: map building on a second stream, overlapping the convs)")
     ap.add_argument("--conv-streams", type=int, default=2, choices=[1, 2],
                     help="with several frames in flight: 2 gives each context its own conv stream as well")
-    ap.add_argument("--frames-in-flight", type=int, default=2, choices=[1, 2, 3, 4],
+    ap.add_argument("--frames-in-flight", type=int, default=3, choices=[1, 2, 3, 4],
                     help="2: two contexts alternate frames, so the maps of frame f+1 are built while the convs of "
                          "frame f run (throughput mode; each step is still one whole frame); 1: one frame at a time")
+    ap.add_argument("--bracket-every", type=int, default=4,
+                    help="the dominant kernel's launches carry event brackets on every N-th timed step")
     ap.add_argument("--no-graphs", action="store_true",
                     help="issue every launch from the host (default: each context's frame is recorded once into a HIP "
                          "graph and replayed; the steps that carry the dominant kernel's event brackets stay eager)")
@@ -269,7 +271,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        timer.enabled = (i % 4 == 0)
+        timer.enabled = (i % args.bracket_every == 0)
         step(pts, batch, timer)
     t_issued = time.perf_counter()
     torch.cuda.synchronize()
