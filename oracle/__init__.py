@@ -47,6 +47,10 @@ def _load():
     lib.emc2o_build_kmap.argtypes = [c_i32, vp, c_i64, vp, c_i32, c_i64, vp, vp, vp]
     lib.emc2o_spconv.restype = c_i64
     lib.emc2o_spconv.argtypes = [vp, c_i64, vp, vp, vp, c_i32, vp, c_i64, c_i64, c_i32, c_i32, vp]
+    lib.emc2o_invert_kmap.restype = c_i64
+    lib.emc2o_invert_kmap.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, vp]
+    lib.emc2o_bev_flatten.restype = c_i64
+    lib.emc2o_bev_flatten.argtypes = [vp, vp, c_i64, vp, c_i32, c_i32, vp]
     lib.emc2o_project_gather.restype = c_i32
     lib.emc2o_project_gather.argtypes = [vp, c_i32, c_i64, vp, vp, c_i32, c_i32, c_i32, vp, vp, vp]
     _lib = lib
@@ -111,6 +115,31 @@ def build_kmap(kind: int, in_coords: np.ndarray, grid_in: Sequence[int], n_batch
     n_out = _chk(lib.emc2o_build_kmap(int(kind), _p(in_coords), n_in, _p(g_in), int(n_batch), cap,
                                       _p(out_coords), _p(nbr), _p(g_out)), "build_kmap")
     return out_coords[:n_out].copy(), np.ascontiguousarray(nbr[:, :n_out]), tuple(int(g) for g in g_out)
+
+
+def invert_kmap(down: np.ndarray, n_fine: int) -> np.ndarray:
+    """down[27][Vcoarse] (a stride-2 map over n_fine inputs) -> inv[27][n_fine]: the same pairs, read from the fine side."""
+    lib = _load()
+    down = np.ascontiguousarray(down, dtype=np.int32)
+    assert down.ndim == 2 and down.shape[0] == 27
+    n_coarse = down.shape[1]
+    cap_f = max(int(n_fine), 1)
+    inv = np.empty((27, cap_f), np.int32)
+    _chk(lib.emc2o_invert_kmap(_p(down), n_coarse, max(n_coarse, 0), int(n_fine), cap_f, _p(inv)), "invert_kmap")
+    return np.ascontiguousarray(inv[:, :n_fine])
+
+
+def bev_flatten(coords: np.ndarray, feats: np.ndarray, grid: Sequence[int], n_batch: int = 1) -> np.ndarray:
+    """coords[V][4] (b,z,y,x), feats[V][C] -> dense out[B][Gy][Gx][Gz*C] f32, zero where no voxel sits."""
+    lib = _load()
+    coords = np.ascontiguousarray(coords, dtype=np.int32).reshape(-1, 4)
+    feats = np.ascontiguousarray(feats, dtype=np.float32)
+    n, c = feats.shape
+    assert coords.shape[0] == n
+    g = np.asarray(grid, np.int32)
+    out = np.empty((n_batch, int(g[1]), int(g[0]), int(g[2]) * c), np.float32)
+    _chk(lib.emc2o_bev_flatten(_p(coords), _p(feats), n, _p(g), int(n_batch), c, _p(out)), "bev_flatten")
+    return out
 
 
 def spconv(x: np.ndarray, w: np.ndarray, scale: Optional[np.ndarray], shift: Optional[np.ndarray],

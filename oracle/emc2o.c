@@ -12,7 +12,11 @@
  *   - sparse conv (Sec. 3.5, O(N x C_v)): per offset, nested loops, fp64 accumulation, then the
  *     folded-BN affine + ReLU epilogue (Sec. 3.6 graph fusion) in fp64, rounded once to fp32;
  *   - point -> image projection with bilinear gather and zero fill for unmatched points
- *     (Sec. 3.1 / Fig. 5 caption), fp64.
+ *     (Sec. 3.1 / Fig. 5 caption), fp64;
+ *   - inverse (transposed) kernel map for the decoder half of the LiDAR UNet (Sec. 3.1: "a UNet and a
+ *     sparse CNN"): the pairs of a stride-2 map with the roles of input and output swapped;
+ *   - bird's-eye-view flattening of a voxel set (Sec. 3.3, latency-prioritised expert works on BEV
+ *     projections): scatter into a dense, zero-filled, z-collapsed tensor.
  *
  * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
  * defined by IEEE fp32 subtract, divide, floor).
@@ -256,6 +260,61 @@ int64_t emc2o_build_kmap(int32_t kind, const int32_t* in_coords, int64_t n_in, c
       }
   free(in_keys);
   return n_out;
+}
+
+/*
+ * Inverse of a stride-2 map.  The stride-2 map lists pairs (coarse output j, tap k, fine input i =
+ * down[k][j]); the transposed convolution sends the coarse features back along the same pairs:
+ *     y_fine[i] = sum over pairs (j, k, i) of x_coarse[j] * W[k].
+ * As a gather table for the fine sites: inv[k*capacity_fine + i] = j if down[k*capacity_coarse + j] == i,
+ * else -1.  A fine site is read by at most one coarse site per tap (i = 2j - 1 + k fixes j), so the
+ * table is well defined; a second claim on the same entry is reported as an argument error.
+ * Returns the number of pairs, or a negative error.
+ */
+int64_t emc2o_invert_kmap(const int32_t* down, int64_t n_coarse, int64_t capacity_coarse, int64_t n_fine,
+                          int64_t capacity_fine, int32_t* inv) {
+  if (n_coarse < 0 || n_fine < 0 || n_coarse > capacity_coarse || n_fine > capacity_fine) return EMC2O_ERR_ARG;
+  for (int k = 0; k < 27; ++k)
+    for (int64_t i = 0; i < capacity_fine; ++i) inv[(int64_t)k * capacity_fine + i] = -1;
+  int64_t pairs = 0;
+  for (int k = 0; k < 27; ++k)
+    for (int64_t j = 0; j < n_coarse; ++j) {
+      const int32_t i = down[(int64_t)k * capacity_coarse + j];
+      if (i < 0) continue;
+      if (i >= n_fine) return EMC2O_ERR_ARG;
+      if (inv[(int64_t)k * capacity_fine + i] != -1) return EMC2O_ERR_ARG;
+      inv[(int64_t)k * capacity_fine + i] = (int32_t)j;
+      ++pairs;
+    }
+  return pairs;
+}
+
+/*
+ * Bird's-eye-view flattening: out[b][y][x][z*C + c] = feats[v][c] for the voxel v at (b, z, y, x), zero
+ * where no voxel sits.  out is [n_batch][Gy][Gx][Gz*C] float.  Returns the number of voxels placed, or a
+ * negative error (coordinate outside the grid, or two voxels at one cell).
+ */
+int64_t emc2o_bev_flatten(const int32_t* coords, const float* feats, int64_t n, const int32_t grid[3],
+                          int32_t n_batch, int32_t c, float* out) {
+  if (n < 0 || c < 1 || n_batch < 1) return EMC2O_ERR_ARG;
+  const int64_t gx = grid[0], gy = grid[1], gz = grid[2];
+  const int64_t total = (int64_t)n_batch * gy * gx * gz * c;
+  for (int64_t t = 0; t < total; ++t) out[t] = 0.0f;
+  unsigned char* taken = (unsigned char*)calloc((size_t)((int64_t)n_batch * gy * gx * gz > 0 ? (int64_t)n_batch * gy * gx * gz : 1), 1);
+  if (!taken) return EMC2O_ERR_NOMEM;
+  for (int64_t v = 0; v < n; ++v) {
+    const int32_t* q = coords + 4 * v;
+    if (q[0] < 0 || q[0] >= n_batch || q[1] < 0 || q[1] >= gz || q[2] < 0 || q[2] >= gy || q[3] < 0 || q[3] >= gx) {
+      free(taken);
+      return EMC2O_ERR_ARG;
+    }
+    const int64_t cell = (((int64_t)q[0] * gy + q[2]) * gx + q[3]) * gz + q[1];
+    if (taken[cell]) { free(taken); return EMC2O_ERR_ARG; }
+    taken[cell] = 1;
+    for (int32_t ch = 0; ch < c; ++ch) out[cell * c + ch] = feats[v * c + ch];
+  }
+  free(taken);
+  return n;
 }
 
 /* ------------------------------------------------------------------------------------------- */
