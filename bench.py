@@ -358,6 +358,58 @@ def main() -> int:
     except Exception as exc:  # the side measurement must never take the headline number down with it
         pg = {"error": repr(exc)}
 
+    # Decoder-side calls on this frame's levels (outside the timed region): the inverse map of the last stride-2
+    # layer, the transposed 64->64 conv over it, and the bird's-eye-view flattening of the coarsest level.
+    dec = None
+    try:
+        runner.run(pts, batch)
+        torch.cuda.synchronize()
+        fine, coarse = runner.levels[-2], runner.levels[-1]
+        nf, nc = int(fine.n.item()), int(coarse.n.item())
+        inv = torch.empty((27, fine.cap), dtype=torch.int32, device="cuda")
+        x_c = runner.acts[-1]
+        cch = int(x_c.shape[1])
+        w_t = torch.randn((27, cch, cch), device="cuda").mul_(0.1).to(x_c.dtype)
+        sc = torch.full((cch,), 0.1, dtype=torch.float32, device="cuda")
+        sh = torch.zeros((cch,), dtype=torch.float32, device="cuda")
+        lay = B.W_PLAIN
+        if ctx.uses_mfma(cfg.dtype, cch, cch):
+            w_p = torch.empty_like(w_t)
+            ctx.pack_weights(cfg.dtype, w_t, w_p)
+            w_t, lay = w_p, B.W_PACKED
+        y_f = torch.empty((fine.cap, cch), dtype=x_c.dtype, device="cuda")
+        bev = torch.empty((br.spec.n_batch, coarse.grid[1], coarse.grid[0], coarse.grid[2] * cch), dtype=x_c.dtype, device="cuda")
+
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0_.record()
+            for _ in range(reps):
+                fn()
+            e1_.record()
+            torch.cuda.synchronize()
+            return e0_.elapsed_time(e1_) / reps
+
+        ms_inv = timed(lambda: ctx.build_inverse_kmap(fine.coords, fine.n, fine.cap, coarse.grid, br.spec.n_batch, coarse.slot, coarse.n, inv))
+        pairs_t = int((inv[:, :nf] >= 0).sum().item())
+        ms_tc = timed(lambda: ctx.spconv(cfg.dtype, x_c, w_t, sc, sh, 2, inv, fine.n, fine.cap, y_f, w_layout=lay))
+        ms_bev = timed(lambda: ctx.bev_flatten(cfg.dtype, coarse.coords, x_c, coarse.n, coarse.cap, coarse.grid, br.spec.n_batch, bev))
+        esz = x_c.element_size()
+        inv_bytes = nf * (16.0 + 108.0)
+        bev_bytes = bev.numel() * esz + nc * (16.0 + 2.0 * cch * esz)
+        fl_t = 2.0 * pairs_t * cch * cch
+        dec = {"inverse_kmap": {"fine": nf, "coarse": nc, "ms": ms_inv, "algorithmic_MB": inv_bytes / 1e6,
+                                "GB/s": inv_bytes / (ms_inv * 1e-3) / 1e9, "frac_of_hbm_peak": inv_bytes / (ms_inv * 1e-3) / 1e9 / PEAK_HBM_GBS},
+               "transposed_conv": {"cin": cch, "cout": cch, "pairs": pairs_t, "ms": ms_tc, "kernel": ctx.spconv_kernel(cfg.dtype, cch, cch),
+                                   "useful_tflops": fl_t / (ms_tc * 1e-3) / 1e12, "frac_of_mfma_peak": fl_t / (ms_tc * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS},
+               "bev_flatten": {"voxels": nc, "dense_MB": bev.numel() * esz / 1e6, "ms": ms_bev, "algorithmic_MB": bev_bytes / 1e6,
+                               "GB/s": bev_bytes / (ms_bev * 1e-3) / 1e9, "frac_of_hbm_peak": bev_bytes / (ms_bev * 1e-3) / 1e9 / PEAK_HBM_GBS}}
+        del inv, y_f, bev, w_t
+    except Exception as exc:
+        dec = {"error": repr(exc)}
+
     # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
     # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
     vox_scaling = []
@@ -414,6 +466,7 @@ def main() -> int:
         "conv_useful_tflops": total_flops / (stage_ms.get("conv", 0.0) * 1e-3) / 1e12 if stage_ms.get("conv") else None,
         "memory_bound_stages": stage_hbm,
         "project_gather": pg,
+        "decoder_side": dec,
         "voxelize_scaling": vox_scaling,
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
                          "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),

@@ -184,6 +184,36 @@ emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const
                         int32_t cin, int32_t cout, void* d_out, void* stream);
 
 /*
+ * Inverse (transposed) kernel map of a stride-2 layer, for the decoder half of the LiDAR UNet (paper
+ * Sec. 3.1: the data bridge extracts LiDAR features with a UNet and a sparse CNN).  The stride-2 map
+ * pairs coarse output j with fine input i = 2j - 1 + (kx, ky, kz) at tap k; the transposed convolution
+ * sends coarse features back along the same pairs, y_fine[i] = sum_{(j,k,i)} x_coarse[j] * W[k], which is
+ * emc2_spconv over the table built here:
+ *   d_nbr[k*capacity_fine + i] = index of the coarse voxel at (i + 1 - k)/2 if that is integral on every
+ *   axis and the coarse cell is active, else -1.
+ *   d_fine_coords [n_fine][4] (b, z, y, x), d_n_fine device count: the sites that receive features.
+ *   coarse_slot: index slot holding the cell index of the coarse level (the out_slot of the
+ *   emc2_build_kmap(STRIDED) call that produced it); grid_coarse its grid; d_n_coarse its device count.
+ * Integer work only; rows [n_fine, capacity_fine) of d_nbr are not written.
+ */
+emc2_status emc2_build_inverse_kmap(emc2_ctx* ctx, const int32_t* d_fine_coords, const int32_t* d_n_fine,
+                                    int64_t capacity_fine, const int32_t grid_coarse[3], int32_t n_batch,
+                                    int32_t coarse_slot, const int32_t* d_n_coarse, int32_t* d_nbr, void* stream);
+
+/*
+ * Bird's-eye-view flattening (paper Sec. 3.3: the latency-prioritised expert runs 2D CNNs on BEV
+ * projections; Sec. 3.2: LiDAR information "compressed into bird's eye view"): the voxel set becomes a
+ * dense, zero-filled tensor with the height axis folded into the channels,
+ *   d_out[b][y][x][z*C + c] = d_feats[v][c]  for the voxel v at (b, z, y, x),   0 where no voxel sits.
+ *   d_out [n_batch][Gy][Gx][Gz*C] of `dtype` (fully written by the call); d_feats [n][C] of `dtype`;
+ *   C*sizeof(dtype) must be a multiple of 4.  Voxels with coordinates outside the grid are ignored.
+ * A copy: bit-exact in every dtype.
+ */
+emc2_status emc2_bev_flatten(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_coords, const void* d_feats,
+                             const int32_t* d_n, int64_t capacity, const int32_t grid[3], int32_t n_batch,
+                             int32_t channels, void* d_out, void* stream);
+
+/*
  * Point -> image projection with bilinear feature gather (paper Sec. 3.1: image features are
  * aligned with 3D positions for fusion; Fig. 5 caption: sites without a match get zero-filled
  * features).

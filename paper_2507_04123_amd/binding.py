@@ -28,7 +28,7 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
-           "emc2_spconv_kernel"]
+           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten"]
 
 
 class Emc2Error(RuntimeError):
@@ -79,6 +79,10 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_spconv_uses_mfma.argtypes = [ctypes.c_int, i32, i32]
     lib.emc2_project_gather.restype = ctypes.c_int
     lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
+    lib.emc2_build_inverse_kmap.restype = ctypes.c_int
+    lib.emc2_build_inverse_kmap.argtypes = [vp, vp, vp, i64, ctypes.POINTER(i32), i32, i32, vp, vp, vp]
+    lib.emc2_bev_flatten.restype = ctypes.c_int
+    lib.emc2_bev_flatten.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, ctypes.POINTER(i32), i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -179,6 +183,37 @@ class Context:
                                            out_slot, capacity_out, _ptr(out_coords), _ptr(n_out), _ptr(nbr), g_out,
                                            ctypes.byref(h_n) if sync_count else None, _stream()))
         return (g_out[0], g_out[1], g_out[2]), (int(h_n.value) if sync_count else None)
+
+    def build_inverse_kmap(self, fine_coords: torch.Tensor, n_fine: torch.Tensor, capacity_fine: int,
+                           grid_coarse: Sequence[int], n_batch: int, coarse_slot: int, n_coarse: torch.Tensor,
+                           nbr: torch.Tensor) -> None:
+        """Gather table of the transposed stride-2 conv: nbr[27][capacity_fine] over the fine sites."""
+        _dev_check(fine_coords, torch.int32, "fine_coords")
+        _dev_check(n_fine, torch.int32, "n_fine")
+        _dev_check(n_coarse, torch.int32, "n_coarse")
+        _dev_check(nbr, torch.int32, "nbr")
+        if fine_coords.numel() < 4 * capacity_fine or nbr.numel() < 27 * capacity_fine:
+            raise ValueError("buffers smaller than capacity_fine")
+        g = (ctypes.c_int32 * 3)(*grid_coarse)
+        self._chk(self.lib.emc2_build_inverse_kmap(self.h, _ptr(fine_coords), _ptr(n_fine), capacity_fine, g, n_batch,
+                                                   coarse_slot, _ptr(n_coarse), _ptr(nbr), _stream()))
+
+    def bev_flatten(self, dtype: int, coords: torch.Tensor, feats: torch.Tensor, n: torch.Tensor, capacity: int,
+                    grid: Sequence[int], n_batch: int, out: torch.Tensor) -> None:
+        """out[B][Gy][Gx][Gz*C] <- feats[v][C] at (b, z, y, x) = coords[v], zero elsewhere."""
+        td = _TORCH_DTYPE[dtype]
+        _dev_check(coords, torch.int32, "coords")
+        _dev_check(feats, td, "feats")
+        _dev_check(out, td, "out")
+        _dev_check(n, torch.int32, "n")
+        c = int(feats.shape[1])
+        if coords.numel() < 4 * capacity or feats.numel() < capacity * c:
+            raise ValueError("coords / feats smaller than capacity")
+        if out.numel() != n_batch * grid[0] * grid[1] * grid[2] * c:
+            raise ValueError("out must be [n_batch][Gy][Gx][Gz*C]")
+        g = (ctypes.c_int32 * 3)(*grid)
+        self._chk(self.lib.emc2_bev_flatten(self.h, dtype, _ptr(coords), _ptr(feats), _ptr(n), capacity, g, n_batch, c,
+                                            _ptr(out), _stream()))
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))

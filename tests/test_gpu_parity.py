@@ -629,3 +629,95 @@ def test_graph_replay_matches_eager_runs():
         same(snapshot(runner.graph_out), ref_b if use_b else ref_a, f"replay {it}")
         same(snapshot(runner.run_overlapped(frame, None)), ref_b if use_b else ref_a, f"eager after replay {it}")
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------------
+# decoder side: inverse (transposed) kernel map, transposed conv, bird's-eye-view flattening
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("grid,nb,n", [((12, 9, 7), 2, 400), ((16, 16, 8), 1, 1500), ((5, 4, 3), 3, 60), ((33, 1, 2), 1, 40)])
+def test_inverse_kmap_and_transposed_conv_small(grid, nb, n):
+    fine = _rand_sites(900 + n, grid, nb, n)
+    ctx = B.Context(16, 8 * len(fine) + 64, cells_of(grid, nb), n_slots=2)
+    coarse, down, gout = oracle.build_kmap(STRIDED, fine, grid, nb)
+    exp_inv = oracle.invert_kmap(down, len(fine))
+    cap_f, cap_c = len(fine) + 13, len(coarse) + 7
+    d_fine = torch.zeros((cap_f, 4), dtype=torch.int32, device="cuda"); d_fine[:len(fine)] = dev(fine)
+    n_f = torch.tensor([len(fine)], dtype=torch.int32, device="cuda")
+    d_coarse = torch.zeros((cap_c, 4), dtype=torch.int32, device="cuda")
+    n_c = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_down = torch.full((27, cap_c), -5, dtype=torch.int32, device="cuda")
+    ctx.build_kmap(B.STRIDED, d_fine, n_f, cap_f, grid, nb, cap_c, d_down, n_c, out_coords=d_coarse, in_slot=-1, out_slot=1)
+    d_inv = torch.full((27, cap_f), -5, dtype=torch.int32, device="cuda")
+    print(f"inverse kmap grid={grid} B={nb} fine={len(fine)} coarse={len(coarse)}", flush=True)
+    ctx.build_inverse_kmap(d_fine, n_f, cap_f, gout, nb, 1, n_c, d_inv)
+    torch.cuda.synchronize()
+    ctx.status_sync()
+    assert int(n_c.item()) == len(coarse)
+    assert np.array_equal(d_inv[:, :len(fine)].cpu().numpy(), exp_inv)
+    assert torch.all(d_inv[:, len(fine):] == -5)                   # rows past n_fine untouched
+    # transposed conv = the ordinary conv kernel over the inverse table, coarse features in, fine features out
+    for dtype, cin, cout in ((F16, 64, 64), (F32, 5, 7), (BF16, 64, 32)):
+        st = gen.Stream(cin * 31 + cout, 2)
+        x = gen.round_to_dtype(st.normal(len(coarse) * cin).astype(np.float32).reshape(-1, cin), dtype)
+        w = gen.round_to_dtype(st.normal(27 * cin * cout, 0.1).astype(np.float32).reshape(27, cin, cout), dtype)
+        scale = (st.uniform(cout, 0.8, 1.2) / (0.1 * np.sqrt(2.0 * cin))).astype(np.float32)
+        shift = st.uniform(cout, -0.1, 0.1).astype(np.float32)
+        exp = oracle.spconv(x, w, scale, shift, EPI_AFFINE_RELU, exp_inv)
+        got = gpu_spconv(ctx, dtype, x, w, scale, shift, EPI_AFFINE_RELU, exp_inv, cap=cap_f, packed=ctx.uses_mfma(dtype, cin, cout))
+        assert_features_close(got[:len(fine)].float().cpu().numpy(), exp, RTOL[dtype], f"transposed conv {cin}->{cout}")
+    with pytest.raises(B.Emc2Error):
+        ctx.build_inverse_kmap(d_fine, n_f, cap_f, gout, nb, 0, n_c, d_inv)       # slot 0 holds no index of the coarse grid
+    ctx.close()
+
+
+def test_inverse_kmap_config2_levels_full_size():
+    """The three stride-2 layers of the front-view backbone, inverted at full size, against the oracle."""
+    cfg = get_config(2)
+    br = cfg.branches[0]
+    pts_np, _ = gen.make_frames(cfg)
+    caps = default_capacities(br, len(pts_np))
+    ctx = B.Context(len(pts_np), max(caps), cells_of(br.spec.grid, 1), n_slots=len(caps))
+    runner = BranchRunner(ctx, br, cfg.dtype, len(pts_np), device_params(br.layers, gen.frame_seed(2, 0), cfg.dtype), capacities=caps)
+    runner.run(dev(pts_np), None)
+    ctx.status_sync()
+    for lvl in range(1, len(runner.levels)):
+        fine, coarse = runner.levels[lvl - 1], runner.levels[lvl]
+        nf, nc = int(fine.n.item()), int(coarse.n.item())
+        inv = torch.full((27, fine.cap), -5, dtype=torch.int32, device="cuda")
+        print(f"inverse kmap level {lvl}->{lvl - 1}: coarse {nc} -> fine {nf}", flush=True)
+        ctx.build_inverse_kmap(fine.coords, fine.n, fine.cap, coarse.grid, 1, coarse.slot, coarse.n, inv)
+        torch.cuda.synchronize()
+        exp = oracle.invert_kmap(coarse.down_nbr[:, :nc].cpu().numpy(), nf)
+        assert np.array_equal(inv[:, :nf].cpu().numpy(), exp)
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,c", [(F32, 4), (F16, 64), (BF16, 6), (F16, 2)])
+def test_bev_flatten_is_an_exact_copy(dtype, c):
+    ctx = B.Context(16, 16, 64, n_slots=1)
+    for grid, nb, n in (((7, 5, 3), 2, 90), ((176, 200, 5), 1, 20000), ((3, 3, 1), 1, 0)):
+        coords = _rand_sites(5 * c + n, grid, nb, n) if n else np.zeros((0, 4), np.int32)
+        st = gen.Stream(c + n, 4)
+        feats = gen.round_to_dtype(st.normal(max(len(coords), 1) * c).astype(np.float32).reshape(-1, c), dtype)[:len(coords)]
+        cap = len(coords) + 9
+        d_c = torch.full((cap, 4), 1 << 20, dtype=torch.int32, device="cuda")      # rows past n: never read
+        d_f = torch.full((cap, c), 3.0, dtype=TD[dtype], device="cuda")
+        if len(coords):
+            d_c[:len(coords)] = dev(coords)
+            d_f[:len(coords)] = dev(feats, TD[dtype])
+        n_t = torch.tensor([len(coords)], dtype=torch.int32, device="cuda")
+        out = torch.full((nb, grid[1], grid[0], grid[2] * c), 9.0, dtype=TD[dtype], device="cuda")
+        print(f"bev_flatten dtype={dtype} C={c} grid={grid} B={nb} n={len(coords)}", flush=True)
+        ctx.bev_flatten(dtype, d_c, d_f, n_t, cap, grid, nb, out)
+        torch.cuda.synchronize()
+        exp = oracle.bev_flatten(coords, feats, grid, nb)
+        assert np.array_equal(out.float().cpu().numpy(), exp)       # a copy: bit-exact (values are dtype-representable)
+    # malformed coordinates are ignored, not written out of bounds
+    bad = torch.tensor([[0, 0, 0, 0], [0, 9, 0, 0], [5, 0, 0, 0], [0, 0, -1, 0]], dtype=torch.int32, device="cuda")
+    f = torch.ones((4, c), dtype=TD[dtype], device="cuda")
+    out = torch.full((1, 2, 2, 2 * c), 9.0, dtype=TD[dtype], device="cuda")
+    ctx.bev_flatten(dtype, bad, f, torch.tensor([4], dtype=torch.int32, device="cuda"), 4, (2, 2, 2), 1, out)
+    torch.cuda.synchronize()
+    assert float(out.float().sum().item()) == float(c)
+    ctx.close()
