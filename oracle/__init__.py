@@ -51,6 +51,11 @@ def _load():
     lib.emc2o_invert_kmap.argtypes = [vp, c_i64, c_i64, c_i64, c_i64, vp]
     lib.emc2o_bev_flatten.restype = c_i64
     lib.emc2o_bev_flatten.argtypes = [vp, vp, c_i64, vp, c_i32, c_i32, vp]
+    lib.emc2o_pool_image.restype = c_i64
+    lib.emc2o_pool_image.argtypes = [vp, vp, c_i32, c_i32, c_i32, vp, vp, vp, vp, c_i32, c_i32, c_i32, c_i64, vp, vp,
+                                     vp, vp]
+    lib.emc2o_fuse.restype = c_i64
+    lib.emc2o_fuse.argtypes = [vp, vp, c_i64, c_i32, vp, vp, c_i64, c_i32, vp, c_i32, c_i64, vp, vp, vp, vp]
     lib.emc2o_project_gather.restype = c_i32
     lib.emc2o_project_gather.argtypes = [vp, c_i32, c_i64, vp, vp, c_i32, c_i32, c_i32, vp, vp, vp]
     _lib = lib
@@ -140,6 +145,57 @@ def bev_flatten(coords: np.ndarray, feats: np.ndarray, grid: Sequence[int], n_ba
     out = np.empty((n_batch, int(g[1]), int(g[0]), int(g[2]) * c), np.float32)
     _chk(lib.emc2o_bev_flatten(_p(coords), _p(feats), n, _p(g), int(n_batch), c, _p(out)), "bev_flatten")
     return out
+
+
+POOL_MEAN, POOL_MAX = 0, 1
+
+
+def pool_image(img: np.ndarray, depth: np.ndarray, qmat: np.ndarray, lo: Sequence[float], vs: Sequence[float],
+               grid: Sequence[int], mode: int = POOL_MEAN, n_batch: int = 1, batch_index: int = 0,
+               capacity: Optional[int] = None, want_xyz: bool = False):
+    """img[H][W][C] (any float; up-cast to f32), depth[H][W] f32, qmat[12] f32 (pixel*depth -> LiDAR frame)
+    -> (coords[N][4], feats[N][C] f32, counts[N][, xyz[H][W][3] f32]), cells in ascending key order."""
+    lib = _load()
+    img32 = np.ascontiguousarray(img.astype(np.float32))
+    h, wd, c = img32.shape
+    depth = np.ascontiguousarray(depth, dtype=np.float32)
+    assert depth.shape == (h, wd)
+    qmat = np.ascontiguousarray(qmat, dtype=np.float32).reshape(12)
+    lo_a, vs_a, g = np.asarray(lo, np.float32), np.asarray(vs, np.float32), np.asarray(grid, np.int32)
+    cap = int(capacity) if capacity is not None else max(h * wd, 1)
+    coords = np.empty((cap, 4), np.int32)
+    feats = np.empty((cap, c), np.float32)
+    counts = np.empty((cap,), np.int32)
+    xyz = np.empty((h, wd, 3), np.float32) if want_xyz else None
+    n = _chk(lib.emc2o_pool_image(_p(img32), _p(depth), h, wd, c, _p(qmat), _p(lo_a), _p(vs_a), _p(g), int(n_batch),
+                                  int(batch_index), int(mode), cap, _p(coords), _p(feats), _p(counts), _p(xyz)),
+             "pool_image")
+    res = (coords[:n].copy(), feats[:n].copy(), counts[:n].copy())
+    return res + (xyz,) if want_xyz else res
+
+
+def fuse(coords_l: np.ndarray, feats_l: np.ndarray, coords_i: np.ndarray, feats_i: np.ndarray, grid: Sequence[int],
+         n_batch: int = 1, capacity: Optional[int] = None, want_src: bool = False):
+    """Union of two key-sorted sparse sets with concatenated features [LiDAR | image], zero-filled halves.
+    -> (coords[N][4], feats[N][Cl+Ci] f32[, src_l[N], src_i[N]])."""
+    lib = _load()
+    coords_l = np.ascontiguousarray(coords_l, dtype=np.int32).reshape(-1, 4)
+    coords_i = np.ascontiguousarray(coords_i, dtype=np.int32).reshape(-1, 4)
+    feats_l = np.ascontiguousarray(feats_l, dtype=np.float32)
+    feats_i = np.ascontiguousarray(feats_i, dtype=np.float32)
+    n_l, cl = feats_l.shape
+    n_i, ci = feats_i.shape
+    assert coords_l.shape[0] == n_l and coords_i.shape[0] == n_i
+    g = np.asarray(grid, np.int32)
+    cap = int(capacity) if capacity is not None else max(n_l + n_i, 1)
+    coords = np.empty((cap, 4), np.int32)
+    feats = np.empty((cap, cl + ci), np.float32)
+    src_l = np.empty((cap,), np.int32) if want_src else None
+    src_i = np.empty((cap,), np.int32) if want_src else None
+    n = _chk(lib.emc2o_fuse(_p(coords_l), _p(feats_l), n_l, cl, _p(coords_i), _p(feats_i), n_i, ci, _p(g),
+                            int(n_batch), cap, _p(coords), _p(feats), _p(src_l), _p(src_i)), "fuse")
+    res = (coords[:n].copy(), feats[:n].copy())
+    return res + (src_l[:n].copy(), src_i[:n].copy()) if want_src else res
 
 
 def spconv(x: np.ndarray, w: np.ndarray, scale: Optional[np.ndarray], shift: Optional[np.ndarray],

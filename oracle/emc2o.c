@@ -16,7 +16,12 @@
  *   - inverse (transposed) kernel map for the decoder half of the LiDAR UNet (Sec. 3.1: "a UNet and a
  *     sparse CNN"): the pairs of a stride-2 map with the roles of input and output swapped;
  *   - bird's-eye-view flattening of a voxel set (Sec. 3.3, latency-prioritised expert works on BEV
- *     projections): scatter into a dense, zero-filled, z-collapsed tensor.
+ *     projections): scatter into a dense, zero-filled, z-collapsed tensor;
+ *   - Multiscale Pooling (Sec. 3.1, Sec. 3.5, Fig. 5): image pixels with depth are lifted into 3D,
+ *     grouped by the cell of a grid of configurable cell size, and their features pooled per cell
+ *     (mean or max);
+ *   - multimodal fusion (Sec. 3.1, Fig. 5 caption): the union of LiDAR voxels and pooled image cells,
+ *     features concatenated, the missing half zero-filled.
  *
  * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
  * defined by IEEE fp32 subtract, divide, floor).
@@ -314,6 +319,145 @@ int64_t emc2o_bev_flatten(const int32_t* coords, const float* feats, int64_t n, 
     for (int32_t ch = 0; ch < c; ++ch) out[cell * c + ch] = feats[v * c + ch];
   }
   free(taken);
+  return n;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Multiscale Pooling and multimodal fusion                                                    */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * Multiscale Pooling of an image feature map into the cells of a voxel grid.
+ *
+ * Pixel (row j, col i) sits at (u, v) = (i, j), as in the projection above.  It is relevant iff its
+ * depth d (distance along the camera's optical axis, the w of the projection) is finite and > 0.
+ * Its 3D position in the LiDAR frame is X = Q (d*u, d*v, d, 1) with Q the 3x4 inverse of the
+ * projection (given, fp32): each row evaluated left to right in fp64 without fused multiply-add,
+ * then rounded once to fp32; the cell is the voxelizer's (fp32 subtract, divide, floor).  Pixels
+ * outside the grid are dropped.  Every cell that receives at least one pixel becomes one output,
+ * in ascending key order:
+ *   coords[c] = (b, z, y, x) with b = batch_index, counts[c] = pixels pooled,
+ *   feats[c][ch] = mode 0: mean over the cell's pixels (fp64 sum, one rounding to fp32)
+ *                  mode 1: max  over the cell's pixels.
+ * xyz (optional, [H][W][3] float): the lifted position of every pixel, NaN where not relevant.
+ * Returns the number of cells or a negative error.
+ */
+int64_t emc2o_pool_image(const float* img, const float* depth, int32_t h, int32_t wd, int32_t c,
+                         const float q[12], const float lo[3], const float vs[3], const int32_t grid[3],
+                         int32_t n_batch, int32_t batch_index, int32_t mode, int64_t capacity,
+                         int32_t* coords, float* feats, int32_t* counts, float* xyz) {
+  if (h < 1 || wd < 1 || c < 1 || n_batch < 1 || batch_index < 0 || batch_index >= n_batch ||
+      (mode != 0 && mode != 1) || grid[0] < 1 || grid[1] < 1 || grid[2] < 1)
+    return EMC2O_ERR_ARG;
+  const int64_t npix = (int64_t)h * wd;
+  keyed_t* ks = (keyed_t*)malloc(sizeof(keyed_t) * (size_t)npix);
+  double* acc = (double*)malloc(sizeof(double) * (size_t)c);
+  if (!ks || !acc) { free(ks); free(acc); return EMC2O_ERR_NOMEM; }
+  int64_t m = 0;
+  for (int64_t j = 0; j < h; ++j) {
+    for (int64_t i = 0; i < wd; ++i) {
+      const int64_t pix = j * wd + i;
+      const float df = depth[pix];
+      float x3[3] = {NAN, NAN, NAN};
+      if (isfinite(df) && df > 0.0f) {
+        const double d = (double)df;
+        const double du = d * (double)i, dv = d * (double)j;
+        for (int r = 0; r < 3; ++r) {
+          const double t = (double)q[4 * r + 0] * du + (double)q[4 * r + 1] * dv +
+                           (double)q[4 * r + 2] * d + (double)q[4 * r + 3];
+          x3[r] = (float)t;
+        }
+        const int cx = cell_of(x3[0], lo[0], vs[0], grid[0]);
+        const int cy = cell_of(x3[1], lo[1], vs[1], grid[1]);
+        const int cz = cell_of(x3[2], lo[2], vs[2], grid[2]);
+        if (cx >= 0 && cy >= 0 && cz >= 0) {
+          ks[m].key = key_of(batch_index, cz, cy, cx, grid);
+          ks[m].idx = pix;
+          ++m;
+        }
+      }
+      if (xyz) { xyz[3 * pix] = x3[0]; xyz[3 * pix + 1] = x3[1]; xyz[3 * pix + 2] = x3[2]; }
+    }
+  }
+  qsort(ks, (size_t)m, sizeof(keyed_t), cmp_keyed);
+  int64_t n = 0, a = 0;
+  while (a < m) {
+    int64_t b = a;
+    while (b < m && ks[b].key == ks[a].key) ++b;
+    if (n >= capacity) { free(ks); free(acc); return EMC2O_ERR_CAPACITY; }
+    for (int ch = 0; ch < c; ++ch) acc[ch] = mode == 0 ? 0.0 : -INFINITY;
+    for (int64_t t = a; t < b; ++t) {
+      const float* row = img + ks[t].idx * c;
+      for (int ch = 0; ch < c; ++ch) {
+        if (mode == 0) acc[ch] += (double)row[ch];
+        else if ((double)row[ch] > acc[ch]) acc[ch] = (double)row[ch];
+      }
+    }
+    const double cnt = (double)(b - a);
+    for (int ch = 0; ch < c; ++ch) feats[n * c + ch] = (float)(mode == 0 ? acc[ch] / cnt : acc[ch]);
+    uint64_t k = ks[a].key;
+    coords[4 * n + 3] = (int32_t)(k % (uint64_t)grid[0]); k /= (uint64_t)grid[0];
+    coords[4 * n + 2] = (int32_t)(k % (uint64_t)grid[1]); k /= (uint64_t)grid[1];
+    coords[4 * n + 1] = (int32_t)(k % (uint64_t)grid[2]); k /= (uint64_t)grid[2];
+    coords[4 * n + 0] = (int32_t)k;
+    counts[n] = (int32_t)(b - a);
+    ++n;
+    a = b;
+  }
+  free(ks);
+  free(acc);
+  return n;
+}
+
+/* Keys of a coordinate list that must be strictly ascending and inside the grid; NULL on violation. */
+static uint64_t* checked_keys(const int32_t* coords, int64_t n, const int32_t grid[3], int32_t n_batch) {
+  uint64_t* keys = (uint64_t*)malloc(sizeof(uint64_t) * (size_t)(n > 0 ? n : 1));
+  if (!keys) return NULL;
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t* q = coords + 4 * i;
+    if (q[0] < 0 || q[0] >= n_batch || q[1] < 0 || q[1] >= grid[2] || q[2] < 0 || q[2] >= grid[1] ||
+        q[3] < 0 || q[3] >= grid[0]) { free(keys); return NULL; }
+    keys[i] = key_of(q[0], q[1], q[2], q[3], grid);
+    if (i > 0 && keys[i] <= keys[i - 1]) { free(keys); return NULL; }
+  }
+  return keys;
+}
+
+/*
+ * Multimodal fusion of two sparse sets on one grid: LiDAR voxels (coords_l, feats_l[.][cl]) and pooled
+ * image cells (coords_i, feats_i[.][ci]), both in ascending key order.  Output: the union of their
+ * sites in ascending key order, features concatenated [LiDAR | image]; an image cell with no voxel at
+ * its coordinate gets a zero LiDAR half (Fig. 5 caption), a voxel with no image cell a zero image half.
+ * src_l / src_i (optional): index of the row of each input that feeds output row r, or -1.
+ * Returns the number of fused sites, or a negative error.
+ */
+int64_t emc2o_fuse(const int32_t* coords_l, const float* feats_l, int64_t n_l, int32_t cl,
+                   const int32_t* coords_i, const float* feats_i, int64_t n_i, int32_t ci,
+                   const int32_t grid[3], int32_t n_batch, int64_t capacity, int32_t* coords, float* feats,
+                   int32_t* src_l, int32_t* src_i) {
+  if (n_l < 0 || n_i < 0 || cl < 1 || ci < 1 || n_batch < 1) return EMC2O_ERR_ARG;
+  uint64_t* kl = checked_keys(coords_l, n_l, grid, n_batch);
+  uint64_t* ki = checked_keys(coords_i, n_i, grid, n_batch);
+  if (!kl || !ki) { free(kl); free(ki); return EMC2O_ERR_ARG; }
+  const int32_t cf = cl + ci;
+  int64_t a = 0, b = 0, n = 0;
+  while (a < n_l || b < n_i) {
+    /* the smaller head key comes next; equal keys are one site fed by both */
+    const int take_l = a < n_l && (b >= n_i || kl[a] <= ki[b]);
+    const int take_i = b < n_i && (a >= n_l || ki[b] <= kl[a]);
+    if (n >= capacity) { free(kl); free(ki); return EMC2O_ERR_CAPACITY; }
+    const int32_t* q = take_l ? coords_l + 4 * a : coords_i + 4 * b;
+    for (int t = 0; t < 4; ++t) coords[4 * n + t] = q[t];
+    for (int ch = 0; ch < cl; ++ch) feats[n * cf + ch] = take_l ? feats_l[a * cl + ch] : 0.0f;
+    for (int ch = 0; ch < ci; ++ch) feats[n * cf + cl + ch] = take_i ? feats_i[b * ci + ch] : 0.0f;
+    if (src_l) src_l[n] = take_l ? (int32_t)a : -1;
+    if (src_i) src_i[n] = take_i ? (int32_t)b : -1;
+    a += take_l;
+    b += take_i;
+    ++n;
+  }
+  free(kl);
+  free(ki);
   return n;
 }
 

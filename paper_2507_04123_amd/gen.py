@@ -228,3 +228,47 @@ def make_image(height: int, width: int, channels: int, seed: int) -> np.ndarray:
     """img[H][W][C] float16 ~ N(0, 1) (stand-in for an image-branch feature map)."""
     st = Stream(seed, 3000)
     return st.normal(height * width * channels, 1.0).astype(np.float16).reshape(height, width, channels)
+
+
+def make_unprojection(pmat: np.ndarray) -> np.ndarray:
+    """Inverse of the pinhole matrix as an input of the pooling step: Q float32[12] with
+    X_lidar = Q (d*u, d*v, d, 1) for the pixel (u, v) at depth d.  With P = [M | p4], Q = [M^-1 | -M^-1 p4],
+    inverted in float64 and rounded once."""
+    p = np.asarray(pmat, np.float64).reshape(3, 4)
+    mi = np.linalg.inv(p[:, :3])
+    return np.ascontiguousarray(np.concatenate([mi, -(mi @ p[:, 3:4])], axis=1).astype(np.float32).reshape(12))
+
+
+def make_depth(height: int, width: int, seed: int, proposals_only: bool = False, n_objects: int = 40) -> np.ndarray:
+    """depth[H][W] float32 of a road scene seen by the camera of make_camera: 0 = no depth (sky, or outside
+    every proposal region when `proposals_only`).
+
+    Rows below the horizon (row 187) see a ground plane 1.6 m under the camera, depth 720*1.6/(row - 187)
+    capped at 70 m; `n_objects` upright rectangles (1.8 x 1.6 m at depths 6..60 m, standing on the ground
+    row of their depth) occlude what lies behind them; +-1 % multiplicative noise.  With `proposals_only`
+    only the pixels inside the rectangles grown by half their size keep a depth: the image regions of the
+    3D proposals."""
+    st = Stream(seed, 4000)
+    f, cy, h_cam = 720.0, 187.0, 1.6
+    rows = np.arange(height, dtype=np.float64)[:, None]
+    cols = np.arange(width, dtype=np.float64)[None, :]
+    depth = np.zeros((height, width), np.float64)
+    below = rows > cy + 1.0
+    ground = f * h_cam / np.maximum(rows - cy, 1e-9)
+    depth = np.where(below & (ground <= 70.0), ground, 0.0) * np.ones((1, width))
+    d_obj = np.sort(st.uniform(n_objects, 6.0, 60.0))[::-1]          # far to near: nearer ones overwrite
+    c_col = st.uniform(n_objects, 0.0, float(width))
+    mask = np.zeros((height, width), bool)
+    for d, cc in zip(d_obj, c_col):
+        half_w = 0.9 * f / d
+        top = cy + f * (h_cam - 1.6) / d
+        bot = cy + f * h_cam / d
+        inside = (np.abs(cols - cc) <= half_w) & (rows >= top) & (rows <= bot)
+        depth = np.where(inside, d, depth)
+        grown = (np.abs(cols - cc) <= 1.5 * half_w) & (rows >= top - 0.25 * (bot - top)) & (rows <= bot + 0.25 * (bot - top))
+        mask |= grown
+    noise = 1.0 + 0.01 * (2.0 * st.uniform(height * width, 0.0, 1.0).reshape(height, width) - 1.0)
+    depth = depth * noise
+    if proposals_only:
+        depth = np.where(mask, depth, 0.0)
+    return np.ascontiguousarray(depth.astype(np.float32))

@@ -1,0 +1,263 @@
+"""Pins for the oracle's Multiscale Pooling and multimodal fusion (paper Sec. 3.1: pixels are projected into 3D
+by their depth, pooled, and fused with the LiDAR voxel features; Sec. 3.5: the pooling size is configurable;
+Fig. 5 caption: matching sites are concatenated, the others padded with zeros).
+
+Expected values come from the camera model itself (lifting a pixel and projecting it back must return the
+pixel), from closed forms for a fronto-parallel plane, from numpy group-by code that shares nothing with the
+oracle's sort-and-run loop, from the exact nesting of power-of-two grids, and from dictionary joins."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2507_04123_amd import gen
+
+LO = (0.0, -40.0, -3.0)
+
+
+def _scene(seed, h=60, w=200, c=6, proposals=False):
+    """A small crop-like scene: the generator's camera, its road-scene depth and a random feature map."""
+    pmat = gen.make_camera(seed)
+    # shrink the image but keep the principal point inside it
+    pm = pmat.astype(np.float64).reshape(3, 4).copy()
+    pm[0] += pm[2] * (w / 2 - 620.5)
+    pm[1] += pm[2] * (h / 3 - 187.0)
+    pm = pm.astype(np.float32).reshape(12)
+    full = gen.make_depth(375, 1242, seed, proposals)
+    r0, c0 = 187 - h // 3, 620 - w // 2
+    depth = np.ascontiguousarray(full[r0:r0 + h, c0:c0 + w])
+    img = gen.make_image(h, w, c, seed)
+    return pm, gen.make_unprojection(pm), depth, img
+
+
+def test_lifted_pixels_project_back_onto_themselves():
+    """Unprojection is pinned to the camera model of the point->image step: P (Q (du, dv, d, 1), 1) = d (u, v, 1)."""
+    pm, q, depth, img = _scene(3)
+    _, _, _, xyz = oracle.pool_image(img, depth, q, LO, (0.2, 0.2, 0.2), (400, 400, 40), want_xyz=True)
+    h, w = depth.shape
+    rel = np.isfinite(depth) & (depth > 0)
+    assert rel.sum() > 1000 and (~rel).sum() > 100
+    assert np.all(np.isnan(xyz[~rel])) and np.all(np.isfinite(xyz[rel]))
+    pts = np.concatenate([xyz[rel], np.zeros((rel.sum(), 1), np.float32)], axis=1)
+    _, _, uv = oracle.project_gather(pts, pm, np.zeros((h, w, 2), np.float16), want_uv=True)
+    jj, ii = np.nonzero(rel)
+    assert np.abs(uv[:, 0] - ii).max() < 2e-2 and np.abs(uv[:, 1] - jj).max() < 2e-2   # fp32 Q and fp32 X
+    # and the depth comes back as the third homogeneous coordinate
+    p = pm.astype(np.float64).reshape(3, 4)
+    wz = pts[:, :3].astype(np.float64) @ p[2, :3] + p[2, 3]
+    assert np.allclose(wz, depth[rel], rtol=1e-4)
+
+
+def test_fronto_parallel_plane_closed_form():
+    """Camera looking along +x from the origin, no rotation besides the axis swap: pixel (u, v) at depth d lifts to
+    (d, -(u - cx) d / f, -(v - cy) d / f).  A constant-depth image is a plane x = d."""
+    f, cx, cy, d = 100.0, 32.3, 20.3, 10.0      # off-integer principal point: no pixel lifts onto a cell border
+    k = np.array([[f, 0, cx], [0, f, cy], [0, 0, 1.0]])
+    r = np.array([[0.0, -1, 0], [0, 0, -1], [1, 0, 0]])
+    pm = (k @ np.concatenate([r, np.zeros((3, 1))], axis=1)).astype(np.float32).reshape(12)
+    q = gen.make_unprojection(pm)
+    h, w, c = 40, 64, 3
+    depth = np.full((h, w), d, np.float32)
+    depth[0, :] = 0.0                      # no depth
+    depth[1, :] = -5.0                     # behind the camera: not relevant
+    depth[2, 0] = np.nan
+    depth[2, 1] = np.inf
+    img = gen.make_image(h, w, c, 1)
+    vs = (0.5, 0.25, 0.25)
+    grid = (40, 64, 32)
+    lo = (0.0, -8.0, -4.0)
+    coords, feats, counts, xyz = oracle.pool_image(img, depth, q, lo, vs, grid, oracle.POOL_MEAN, want_xyz=True)
+    jj, ii = np.mgrid[0:h, 0:w]
+    ok = depth == d
+    assert np.allclose(xyz[ok][:, 0], d, atol=1e-4)
+    assert np.allclose(xyz[ok][:, 1], (-(ii - cx) * d / f)[ok], atol=1e-4)
+    assert np.allclose(xyz[ok][:, 2], (-(jj - cy) * d / f)[ok], atol=1e-4)
+    # every cell sits in the slab x = floor(10 / 0.5) = 20; pixel pitch d/f = 0.1 m -> 2.5 pixels per 0.25 m cell
+    assert np.all(coords[:, 3] == 20) and np.all(coords[:, 0] == 0)
+    assert counts.sum() == ok.sum() and counts.max() <= 9 and counts.min() >= 1
+    # y cell of column u: floor((-(u - cx) * 0.1 + 8) / 0.25), likewise z from the row
+    y_exact = (-(ii - cx) * d / f - lo[1]) / vs[1]
+    z_exact = (-(jj - cy) * d / f - lo[2]) / vs[2]
+    safe = ok & (np.abs(y_exact - np.round(y_exact)) > 1e-3) & (np.abs(z_exact - np.round(z_exact)) > 1e-3)
+    lut = {tuple(cc): n for n, cc in enumerate(coords.tolist())}
+    sums = np.zeros((len(coords), c)); seen = np.zeros(len(coords), int)
+    unsafe_cells = set()
+    for j, i in zip(*np.nonzero(ok)):
+        cell = (0, int(np.floor(z_exact[j, i])), int(np.floor(y_exact[j, i])), 20)
+        if not safe[j, i]:
+            unsafe_cells.add(cell)
+            for dz in (-1, 0, 1):
+                for dy in (-1, 0, 1):
+                    unsafe_cells.add((0, cell[1] + dz, cell[2] + dy, 20))
+            continue
+        assert cell in lut
+        sums[lut[cell]] += img[j, i].astype(np.float64); seen[lut[cell]] += 1
+    checked = 0
+    for cell, n in lut.items():
+        if cell in unsafe_cells:
+            continue
+        assert seen[n] == counts[n]
+        assert np.allclose(feats[n], sums[n] / seen[n], rtol=1e-6, atol=1e-7)
+        checked += 1
+    assert checked > 50
+
+
+def _numpy_pool(img, xyz, lo, vs, grid, mode):
+    """Group-by with numpy primitives on the lifted positions: fp32 subtract / divide / floor, np.unique, ufunc.at."""
+    h, w, c = img.shape
+    p = xyz.reshape(-1, 3)
+    rows = img.reshape(-1, c).astype(np.float64)
+    lo32, vs32 = np.asarray(lo, np.float32), np.asarray(vs, np.float32)
+    with np.errstate(invalid="ignore"):
+        t = (p - lo32) / vs32
+        keep = np.all((t >= 0) & (t < np.asarray(grid, np.float32)), axis=1)
+    cell = np.floor(t[keep]).astype(np.int64)
+    key = (cell[:, 2] * grid[1] + cell[:, 1]) * grid[0] + cell[:, 0]
+    uk, inv, cnt = np.unique(key, return_inverse=True, return_counts=True)
+    if mode == oracle.POOL_MEAN:
+        acc = np.zeros((len(uk), c))
+        np.add.at(acc, inv, rows[keep])
+        acc /= cnt[:, None]
+    else:
+        acc = np.full((len(uk), c), -np.inf)
+        np.maximum.at(acc, inv, rows[keep])
+    coords = np.stack([np.zeros_like(uk), uk // (grid[0] * grid[1]), (uk // grid[0]) % grid[1], uk % grid[0]], axis=1)
+    return coords.astype(np.int32), acc, cnt.astype(np.int32)
+
+
+@pytest.mark.parametrize("mode", [oracle.POOL_MEAN, oracle.POOL_MAX])
+@pytest.mark.parametrize("vs,grid", [((0.05, 0.05, 0.1), (1408, 1600, 40)), ((0.2, 0.2, 0.4), (352, 400, 10)),
+                                     ((0.4, 0.4, 0.4), (100, 120, 4))])
+def test_pooling_matches_numpy_group_by(mode, vs, grid):
+    pm, q, depth, img = _scene(5, proposals=(grid[0] == 352))
+    coords, feats, counts, xyz = oracle.pool_image(img, depth, q, LO, vs, grid, mode, want_xyz=True)
+    ec, ef, en = _numpy_pool(img, xyz, LO, vs, grid, mode)
+    assert len(coords) > 20
+    assert np.array_equal(coords, ec) and np.array_equal(counts, en)
+    if mode == oracle.POOL_MAX:
+        assert np.array_equal(feats, ef.astype(np.float32))
+    else:
+        assert np.allclose(feats, ef, rtol=1e-6, atol=1e-7)
+    # ascending key order, no cell twice
+    key = (coords[:, 1].astype(np.int64) * grid[1] + coords[:, 2]) * grid[0] + coords[:, 3]
+    assert np.all(np.diff(key) > 0)
+    # the small grid drops pixels outside it; the others lose none but those
+    inside = int(en.sum())
+    assert counts.sum() == inside <= int((depth > 0).sum())
+
+
+def test_power_of_two_scales_nest_exactly():
+    """Doubling the cell size halves the fp32 quotient exactly, so every coarse cell is the union of its 8 children:
+    counts add, maxima nest, means combine with the counts as weights (the 'multiscale' in the pooling)."""
+    pm, q, depth, img = _scene(9, h=80, w=240, c=5)
+    fine_vs, fine_grid = (0.1, 0.1, 0.2), (704, 800, 20)
+    for mult in (2, 4):
+        vs = tuple(v * mult for v in fine_vs)
+        grid = tuple(g // mult for g in fine_grid)
+        for mode in (oracle.POOL_MEAN, oracle.POOL_MAX):
+            fc, ff, fn = oracle.pool_image(img, depth, q, LO, fine_vs, fine_grid, mode)
+            cc, cf, cn = oracle.pool_image(img, depth, q, LO, vs, grid, mode)
+            parent = {}
+            for n, (b, z, y, x) in enumerate(fc.tolist()):
+                parent.setdefault((b, z // mult, y // mult, x // mult), []).append(n)
+            assert sorted(parent) == [tuple(r) for r in cc.tolist()]
+            for n, cell in enumerate(map(tuple, cc.tolist())):
+                kids = parent[cell]
+                assert cn[n] == fn[kids].sum()
+                if mode == oracle.POOL_MAX:
+                    assert np.array_equal(cf[n], ff[kids].max(axis=0))
+                else:
+                    want = (ff[kids].astype(np.float64) * fn[kids, None]).sum(axis=0) / fn[kids].sum()
+                    assert np.allclose(cf[n], want, rtol=2e-6, atol=1e-6)
+
+
+def test_pooling_degenerate_cases():
+    pm, q, depth, img = _scene(2, h=24, w=48, c=4)
+    # nothing relevant
+    c0, f0, n0 = oracle.pool_image(img, np.zeros_like(depth), q, LO, (0.2, 0.2, 0.2), (400, 400, 40))
+    assert len(c0) == 0 and f0.shape == (0, 4) and len(n0) == 0
+    # one huge cell swallows every relevant pixel: the pooled row is the image's mean / max over them
+    rel = depth > 0
+    big = ((200.0, 200.0, 200.0), (1, 1, 1), (-100.0, -100.0, -100.0))
+    for mode, ref in ((oracle.POOL_MEAN, img[rel].astype(np.float64).mean(axis=0)),
+                      (oracle.POOL_MAX, img[rel].astype(np.float64).max(axis=0))):
+        c1, f1, n1 = oracle.pool_image(img, depth, q, big[2], big[0], big[1], mode)
+        assert c1.tolist() == [[0, 0, 0, 0]] and n1[0] == rel.sum()
+        assert np.allclose(f1[0], ref, rtol=1e-6, atol=1e-7)
+    # frame tag and capacity
+    c2, _, _ = oracle.pool_image(img, depth, q, LO, (0.4, 0.4, 0.4), (200, 200, 20), n_batch=3, batch_index=2)
+    assert len(c2) > 0 and np.all(c2[:, 0] == 2)
+    with pytest.raises(RuntimeError):
+        oracle.pool_image(img, depth, q, LO, (0.4, 0.4, 0.4), (200, 200, 20), capacity=len(c2) - 1)
+    with pytest.raises(RuntimeError):
+        oracle.pool_image(img, depth, q, LO, (0.4, 0.4, 0.4), (200, 200, 20), n_batch=2, batch_index=2)
+
+
+# ------------------------------------------------------------------------------------------------------------
+# fusion
+# ------------------------------------------------------------------------------------------------------------
+
+def _random_set(seed, grid, n_batch, n, c):
+    gx, gy, gz = grid
+    total = gx * gy * gz * n_batch
+    st = gen.Stream(seed, 7)
+    keys = np.unique((st.bits(3 * n) % np.uint64(total)).astype(np.int64))[:n]
+    keys.sort()
+    coords = np.stack([keys // (gx * gy * gz), (keys // (gx * gy)) % gz, (keys // gx) % gy, keys % gx], axis=1).astype(np.int32)
+    feats = st.normal(len(coords) * c).astype(np.float32).reshape(-1, c)
+    return coords, feats
+
+
+@pytest.mark.parametrize("grid,nb,nl,ni", [((9, 7, 5), 2, 200, 150), ((6, 6, 6), 1, 150, 150), ((30, 20, 4), 1, 50, 400),
+                                           ((5, 5, 2), 3, 0, 40), ((5, 5, 2), 3, 40, 0)])
+def test_fusion_is_a_dictionary_join(grid, nb, nl, ni):
+    cl, ci = 3, 5
+    lc, lf = _random_set(1, grid, nb, nl, cl) if nl else (np.zeros((0, 4), np.int32), np.zeros((0, cl), np.float32))
+    ic, if_ = _random_set(2, grid, nb, ni, ci) if ni else (np.zeros((0, 4), np.int32), np.zeros((0, ci), np.float32))
+    coords, feats, src_l, src_i = oracle.fuse(lc, lf, ic, if_, grid, nb, want_src=True)
+    dl = {tuple(c): f for c, f in zip(lc.tolist(), lf)}
+    di = {tuple(c): f for c, f in zip(ic.tolist(), if_)}
+    sites = sorted(set(dl) | set(di), key=lambda s: ((s[0] * grid[2] + s[1]) * grid[1] + s[2]) * grid[0] + s[3])
+    assert [tuple(c) for c in coords.tolist()] == sites
+    assert len(sites) == len(dl) + len(di) - len(set(dl) & set(di))
+    both = 0
+    for n, s in enumerate(sites):
+        assert np.array_equal(feats[n, :cl], dl.get(s, np.zeros(cl, np.float32)))     # zero-filled LiDAR half
+        assert np.array_equal(feats[n, cl:], di.get(s, np.zeros(ci, np.float32)))     # zero-filled image half
+        assert (src_l[n] >= 0) == (s in dl) and (src_i[n] >= 0) == (s in di)
+        if src_l[n] >= 0:
+            assert tuple(lc[src_l[n]]) == s
+        if src_i[n] >= 0:
+            assert tuple(ic[src_i[n]]) == s
+        both += int(s in dl and s in di)
+    if nl and ni:
+        assert both > 0                                                               # the case the caption is about
+
+
+def test_fusion_hand_case_and_errors():
+    grid = (4, 4, 2)
+    lc = np.array([[0, 0, 1, 1], [0, 1, 2, 3]], np.int32)
+    lf = np.array([[1, 2], [3, 4]], np.float32)
+    ic = np.array([[0, 0, 0, 2], [0, 0, 1, 1]], np.int32)
+    if_ = np.array([[10, 20, 30], [40, 50, 60]], np.float32)
+    coords, feats = oracle.fuse(lc, lf, ic, if_, grid)
+    assert coords.tolist() == [[0, 0, 0, 2], [0, 0, 1, 1], [0, 1, 2, 3]]
+    assert feats.tolist() == [[0, 0, 10, 20, 30], [1, 2, 40, 50, 60], [3, 4, 0, 0, 0]]
+    with pytest.raises(RuntimeError):                      # not in key order
+        oracle.fuse(lc[::-1], lf, ic, if_, grid)
+    with pytest.raises(RuntimeError):                      # outside the grid
+        oracle.fuse(lc, lf, np.array([[0, 2, 0, 0], [0, 0, 1, 1]], np.int32), if_, grid)
+    with pytest.raises(RuntimeError):                      # capacity
+        oracle.fuse(lc, lf, ic, if_, grid, capacity=2)
+
+
+def test_pool_then_fuse_on_a_scene():
+    """The two steps chained as in the data bridge: cells pooled on a voxel grid join the voxels of the same grid."""
+    pm, q, depth, img = _scene(4, h=60, w=160, c=4)
+    vs, grid = (0.4, 0.4, 0.4), (176, 200, 10)
+    ic, if_, _ = oracle.pool_image(img, depth, q, LO, vs, grid, oracle.POOL_MAX)
+    pts = gen.make_cloud("front", 4000, 4)
+    lc, lf, _ = oracle.voxelize(pts, None, LO, vs, grid)
+    coords, feats, sl, si = oracle.fuse(lc, lf, ic, if_, grid, want_src=True)
+    assert len(coords) == len(lc) + len(ic) - int(((sl >= 0) & (si >= 0)).sum())
+    assert np.array_equal(feats[sl >= 0, :4], lf) and np.array_equal(feats[si >= 0, 4:], if_)
+    assert not feats[sl < 0, :4].any() and not feats[si < 0, 4:].any()
