@@ -213,6 +213,55 @@ emc2_status emc2_bev_flatten(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_c
                              const int32_t* d_n, int64_t capacity, const int32_t grid[3], int32_t n_batch,
                              int32_t channels, void* d_out, void* stream);
 
+typedef enum { EMC2_POOL_MEAN = 0, EMC2_POOL_MAX = 1 } emc2_pool_mode;
+
+/*
+ * Multiscale Pooling of an image feature map into the cells of a voxel grid (paper Sec. 3.1: the data bridge
+ * projects the relevant image pixels into 3D by their depth and pools them before fusion; Sec. 3.5: the
+ * pooling size is a user parameter, here the cell size spec->vs; Fig. 5).
+ *
+ * Pixel (row j, col i) sits at (u, v) = (i, j), as in emc2_project_gather.  It is relevant iff its depth d
+ * (distance along the optical axis, the w of the projection) is finite and > 0: the caller marks pixels outside
+ * the proposal regions by a depth of 0.  Its position in the LiDAR frame is X = Q (d*u, d*v, d, 1), Q the 3x4
+ * inverse of the projection: each row evaluated left to right in fp64 without fused multiply-add, rounded once
+ * to fp32; its cell is the voxelizer's (t = fl(fl(X_a - lo_a) / vs_a), kept iff 0 <= t < G_a, cell floor(t)).
+ * Every cell that receives a pixel becomes one output, in ascending key order:
+ *   d_coords [capacity][4] int32 (batch_index, z, y, x);  d_counts [capacity] int32 pixels pooled;
+ *   d_feats  [capacity][C] fp16: per channel the mean (fp32 sums, order not fixed, one rounding to fp16) or the
+ *            maximum (exact) over the cell's pixels;
+ *   d_n_cells device int32 (always written); h_n_cells host int32, NULL = no sync.
+ *   d_img [H][W][C] fp16 with finite values, C a multiple of 8 in [8, 256]; d_depth [H][W] fp32; Q host float[12];
+ *   H*W <= max_points.  Of spec only lo, vs, grid and n_batch are used (no range filter).
+ * index_slot: receives the cell index of the produced set (as emc2_voxelize does), so a kernel map can be built
+ * over the pooled cells directly.  EMC2_ERR_CAPACITY through the status word if more than `capacity` cells exist.
+ */
+emc2_status emc2_pool_image(emc2_ctx* ctx, const void* d_img, const float* d_depth, int32_t H, int32_t W, int32_t C,
+                            const float Q[12], const emc2_voxel_spec* spec, int32_t batch_index, emc2_pool_mode mode,
+                            int64_t capacity, int32_t* d_coords, void* d_feats, int32_t* d_counts, int32_t* d_n_cells,
+                            int32_t* h_n_cells, int32_t index_slot, void* stream);
+
+/*
+ * Multimodal fusion of the LiDAR voxels with the pooled image cells of the same grid (paper Sec. 3.1; Fig. 5
+ * caption: image features that share a voxel's 3D coordinate are concatenated with that voxel's features, the
+ * others with zero-filled features).  The output is the union of the two site sets in ascending key order,
+ *   d_feats_out[r] = [ LiDAR row or zeros (c_l) | image row or zeros (c_i) | zeros (c_out - c_l - c_i) ],
+ * a voxel set like any other: its cell index is left in out_slot, so emc2_build_kmap can follow, and c_out may
+ * pad the rows to a channel count the matrix-core convolution takes.
+ *   d_coords_l [n_l][4], d_feats_l [n_l][c_l], d_n_l device count (likewise _i): each a set without repeated
+ *   sites, in any order; coordinates outside the grid are ignored.  All features of `dtype`; c_l, c_i and c_out
+ *   rows must be multiples of 4 bytes (16-byte multiples take the fast path).
+ *   d_coords_out [capacity_out][4], d_feats_out [capacity_out][c_out]; d_src_l / d_src_i [capacity_out] int32 or
+ *   NULL: the input row that feeds output row r, -1 where that half is zero-filled.
+ *   d_n_out device int32 (always written); h_n_out host, NULL = no sync.
+ * A copy: bit-exact in every dtype.  EMC2_ERR_CAPACITY through the status word if the union exceeds capacity_out.
+ */
+emc2_status emc2_fuse(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_coords_l, const void* d_feats_l,
+                      const int32_t* d_n_l, int64_t capacity_l, int32_t c_l, const int32_t* d_coords_i,
+                      const void* d_feats_i, const int32_t* d_n_i, int64_t capacity_i, int32_t c_i,
+                      const int32_t grid[3], int32_t n_batch, int32_t out_slot, int64_t capacity_out, int32_t c_out,
+                      int32_t* d_coords_out, void* d_feats_out, int32_t* d_src_l, int32_t* d_src_i, int32_t* d_n_out,
+                      int32_t* h_n_out, void* stream);
+
 /*
  * Point -> image projection with bilinear feature gather (paper Sec. 3.1: image features are
  * aligned with 3D positions for fusion; Fig. 5 caption: sites without a match get zero-filled

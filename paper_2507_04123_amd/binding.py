@@ -22,13 +22,14 @@ F32, F16, BF16 = 0, 1, 2
 SUBM, STRIDED = 0, 1
 EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
 W_PLAIN, W_PACKED = 0, 1
+POOL_MEAN, POOL_MAX = 0, 1
 MAP_ANY = -1   # emc2_spconv map_hint: SUBM / STRIDED as passed to build_kmap, or unknown
 
 _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
-           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten"]
+           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse"]
 
 
 class Emc2Error(RuntimeError):
@@ -77,6 +78,12 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_spconv_kernel.argtypes = [ctypes.c_int, i32, i32, i32]
     lib.emc2_spconv_uses_mfma.restype = i32
     lib.emc2_spconv_uses_mfma.argtypes = [ctypes.c_int, i32, i32]
+    lib.emc2_pool_image.restype = ctypes.c_int
+    lib.emc2_pool_image.argtypes = [vp, vp, vp, i32, i32, i32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(_VoxelSpecC),
+                                    i32, ctypes.c_int, i64, vp, vp, vp, vp, ctypes.POINTER(i32), i32, vp]
+    lib.emc2_fuse.restype = ctypes.c_int
+    lib.emc2_fuse.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp, vp, i64, i32, ctypes.POINTER(i32), i32, i32,
+                              i64, i32, vp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
     lib.emc2_project_gather.restype = ctypes.c_int
     lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
     lib.emc2_build_inverse_kmap.restype = ctypes.c_int
@@ -214,6 +221,62 @@ class Context:
         g = (ctypes.c_int32 * 3)(*grid)
         self._chk(self.lib.emc2_bev_flatten(self.h, dtype, _ptr(coords), _ptr(feats), _ptr(n), capacity, g, n_batch, c,
                                             _ptr(out), _stream()))
+
+    def pool_image(self, img: torch.Tensor, depth: torch.Tensor, qmat: Sequence[float], spec: VoxelSpec, mode: int,
+                   capacity: int, coords: torch.Tensor, feats: torch.Tensor, counts: torch.Tensor, n_cells: torch.Tensor,
+                   batch_index: int = 0, index_slot: int = 0, sync_count: bool = False) -> Optional[int]:
+        """img[H][W][C] f16 + depth[H][W] f32 -> pooled cells (coords, feats[cap][C] f16, counts) on spec's grid."""
+        _dev_check(img, torch.float16, "img")
+        _dev_check(depth, torch.float32, "depth")
+        _dev_check(coords, torch.int32, "coords")
+        _dev_check(feats, torch.float16, "feats")
+        _dev_check(counts, torch.int32, "counts")
+        _dev_check(n_cells, torch.int32, "n_cells")
+        if img.dim() != 3 or tuple(depth.shape) != tuple(img.shape[:2]):
+            raise ValueError("img must be [H][W][C] and depth [H][W]")
+        h, w, c = (int(v) for v in img.shape)
+        if coords.numel() < 4 * capacity or feats.numel() < capacity * c or counts.numel() < capacity:
+            raise ValueError("output buffers smaller than capacity")
+        q = (ctypes.c_float * 12)(*[float(v) for v in qmat])
+        cs = _VoxelSpecC((ctypes.c_float * 3)(*spec.lo), (ctypes.c_float * 3)(*spec.vs), (ctypes.c_int32 * 3)(*spec.grid),
+                         spec.n_batch, 0.0, float("inf"), 4)
+        h_n = ctypes.c_int32(0)
+        self._chk(self.lib.emc2_pool_image(self.h, _ptr(img), _ptr(depth), h, w, c, q, ctypes.byref(cs), batch_index, mode,
+                                           capacity, _ptr(coords), _ptr(feats), _ptr(counts), _ptr(n_cells),
+                                           ctypes.byref(h_n) if sync_count else None, index_slot, _stream()))
+        return int(h_n.value) if sync_count else None
+
+    def fuse(self, dtype: int, coords_l: torch.Tensor, feats_l: torch.Tensor, n_l: torch.Tensor, capacity_l: int,
+             coords_i: torch.Tensor, feats_i: torch.Tensor, n_i: torch.Tensor, capacity_i: int, grid: Sequence[int],
+             n_batch: int, capacity_out: int, coords_out: torch.Tensor, feats_out: torch.Tensor, n_out: torch.Tensor,
+             src_l: Optional[torch.Tensor] = None, src_i: Optional[torch.Tensor] = None, out_slot: int = 0,
+             sync_count: bool = False) -> Optional[int]:
+        """Union of the LiDAR voxels and the image cells, rows [LiDAR | image | zero padding up to feats_out's width]."""
+        td = _TORCH_DTYPE[dtype]
+        for t, nm in ((coords_l, "coords_l"), (coords_i, "coords_i"), (coords_out, "coords_out"), (n_l, "n_l"), (n_i, "n_i"),
+                      (n_out, "n_out")):
+            _dev_check(t, torch.int32, nm)
+        for t, nm in ((feats_l, "feats_l"), (feats_i, "feats_i"), (feats_out, "feats_out")):
+            _dev_check(t, td, nm)
+        c_l, c_i, c_out = int(feats_l.shape[1]), int(feats_i.shape[1]), int(feats_out.shape[1])
+        if coords_l.numel() < 4 * capacity_l or feats_l.numel() < capacity_l * c_l:
+            raise ValueError("LiDAR buffers smaller than capacity_l")
+        if coords_i.numel() < 4 * capacity_i or feats_i.numel() < capacity_i * c_i:
+            raise ValueError("image buffers smaller than capacity_i")
+        if coords_out.numel() < 4 * capacity_out or feats_out.numel() < capacity_out * c_out:
+            raise ValueError("output buffers smaller than capacity_out")
+        for t, nm in ((src_l, "src_l"), (src_i, "src_i")):
+            if t is not None:
+                _dev_check(t, torch.int32, nm)
+                if t.numel() < capacity_out:
+                    raise ValueError(f"{nm} smaller than capacity_out")
+        g = (ctypes.c_int32 * 3)(*grid)
+        h_n = ctypes.c_int32(0)
+        self._chk(self.lib.emc2_fuse(self.h, dtype, _ptr(coords_l), _ptr(feats_l), _ptr(n_l), capacity_l, c_l, _ptr(coords_i),
+                                     _ptr(feats_i), _ptr(n_i), capacity_i, c_i, g, n_batch, out_slot, capacity_out, c_out,
+                                     _ptr(coords_out), _ptr(feats_out), _ptr(src_l), _ptr(src_i), _ptr(n_out),
+                                     ctypes.byref(h_n) if sync_count else None, _stream()))
+        return int(h_n.value) if sync_count else None
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))

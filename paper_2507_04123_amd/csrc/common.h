@@ -40,8 +40,6 @@ __device__ __forceinline__ int4 decode_key(uint64_t key, int gx, int gy, int gz)
   return make_int4((int)k, z, y, x);
 }
 
-// Voxel hash record (open addressing, linear probing): the key and its running sums share one
-// 32-byte sector so that a point touches a single sector for the CAS and its five atomic adds.
 // points a voxel's stash holds before further ones are added atomically (LiDAR voxels hold 1-2 points)
 #define EMC2_VOX_STASH 4
 
@@ -69,6 +67,13 @@ struct emc2_ctx {
   int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count
   void* wpack;              // scratch for weights re-ordered per call (27*128*128 16-bit values)
   void* zero_row;           // 256 zero bytes: the feature row an absent neighbour reads
+  // image pooling: per-pixel cell rank / position within the cell / sorted order, per-cell list starts
+  int32_t *pix_rank, *pix_pos, *pix_perm, *pix_srank;   // [max_points] each
+  int32_t* cell_start;      // [max_voxels + 1]
+  uint32_t* pool_totals;    // block totals of the scan over the per-cell counts
+  int64_t n_pool_totals;
+  uint32_t* pool_acc;       // [(max_points/64 + 2) * 256] partial results of cells that cross a block boundary
+  int32_t* fuse_src;        // [2 * max_voxels] source rows of a fused set when the caller does not keep them
   int32_t* pinned;          // pinned host staging for counts / status (4 ints)
   char err[256];
 };

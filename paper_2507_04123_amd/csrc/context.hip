@@ -70,6 +70,15 @@ extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_point
   TRY(hipMalloc((void**)&ctx->partials, sizeof(uint32_t) * (size_t)ctx->n_partials), "hipMalloc(partials)");
   TRY(hipMalloc((void**)&ctx->zero_row, 256), "hipMalloc(zero_row)");
   TRY(hipMemset(ctx->zero_row, 0, 256), "hipMemset(zero_row)");
+  TRY(hipMalloc((void**)&ctx->pix_rank, sizeof(int32_t) * 4 * (size_t)max_points), "hipMalloc(pixel scratch)");
+  ctx->pix_pos = ctx->pix_rank + max_points;
+  ctx->pix_perm = ctx->pix_pos + max_points;
+  ctx->pix_srank = ctx->pix_perm + max_points;
+  TRY(hipMalloc((void**)&ctx->cell_start, sizeof(int32_t) * ((size_t)max_voxels + 1)), "hipMalloc(cell_start)");
+  ctx->n_pool_totals = emc2_div_up(max_voxels, 2048) + 1;
+  TRY(hipMalloc((void**)&ctx->pool_totals, sizeof(uint32_t) * (size_t)ctx->n_pool_totals), "hipMalloc(pool_totals)");
+  TRY(hipMalloc((void**)&ctx->pool_acc, sizeof(uint32_t) * 256 * ((size_t)max_points / 64 + 2)), "hipMalloc(pool_acc)");
+  TRY(hipMalloc((void**)&ctx->fuse_src, sizeof(int32_t) * 2 * (size_t)max_voxels), "hipMalloc(fuse_src)");
   TRY(hipMalloc((void**)&ctx->wpack, (size_t)27 * 128 * 128 * 2), "hipMalloc(wpack)");
   TRY(hipMalloc((void**)&ctx->dev_words, sizeof(int32_t) * 8), "hipMalloc(dev_words)");
   TRY(hipMemset(ctx->dev_words, 0, sizeof(int32_t) * 8), "hipMemset(dev_words)");
@@ -96,6 +105,11 @@ extern "C" void emc2_destroy(emc2_ctx* ctx) {
   if (ctx->partials) (void)hipFree(ctx->partials);
   if (ctx->zero_row) (void)hipFree(ctx->zero_row);
   if (ctx->wpack) (void)hipFree(ctx->wpack);
+  if (ctx->pix_rank) (void)hipFree(ctx->pix_rank);
+  if (ctx->cell_start) (void)hipFree(ctx->cell_start);
+  if (ctx->pool_totals) (void)hipFree(ctx->pool_totals);
+  if (ctx->pool_acc) (void)hipFree(ctx->pool_acc);
+  if (ctx->fuse_src) (void)hipFree(ctx->fuse_src);
   if (ctx->dev_words) (void)hipFree(ctx->dev_words);
   if (ctx->pinned) (void)hipHostFree(ctx->pinned);
   free(ctx);

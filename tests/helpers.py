@@ -61,3 +61,16 @@ def oracle_branch(points: np.ndarray, batch, branch: Branch, dtype: int, params)
         acts.append(x)
         maps.append(nbr)
     return {"levels": levels, "means": means, "counts": counts, "acts": acts, "maps": maps}
+
+
+def make_scene(seed, h=60, w=200, c=6, proposals=False):
+    """A crop of the camera scene around the principal point: (pmat, qmat, depth[h][w] f32, img[h][w][c] f16)."""
+    pm = gen.make_camera(seed).astype(np.float64).reshape(3, 4).copy()
+    pm[0] += pm[2] * (w / 2 - 620.5)          # move the principal point to the crop's centre column
+    pm[1] += pm[2] * (h / 3 - 187.0)          # and to a third of its height (the horizon)
+    pm = pm.astype(np.float32).reshape(12)
+    full = gen.make_depth(375, 1242, seed, proposals)
+    r0, c0 = 187 - h // 3, 620 - w // 2
+    depth = np.ascontiguousarray(full[r0:r0 + h, c0:c0 + w])
+    img = gen.make_image(h, w, c, seed)
+    return pm, gen.make_unprojection(pm), depth, img

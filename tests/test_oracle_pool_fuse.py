@@ -9,24 +9,10 @@ import numpy as np
 import pytest
 
 import oracle
+from helpers import make_scene as _scene
 from paper_2507_04123_amd import gen
 
 LO = (0.0, -40.0, -3.0)
-
-
-def _scene(seed, h=60, w=200, c=6, proposals=False):
-    """A small crop-like scene: the generator's camera, its road-scene depth and a random feature map."""
-    pmat = gen.make_camera(seed)
-    # shrink the image but keep the principal point inside it
-    pm = pmat.astype(np.float64).reshape(3, 4).copy()
-    pm[0] += pm[2] * (w / 2 - 620.5)
-    pm[1] += pm[2] * (h / 3 - 187.0)
-    pm = pm.astype(np.float32).reshape(12)
-    full = gen.make_depth(375, 1242, seed, proposals)
-    r0, c0 = 187 - h // 3, 620 - w // 2
-    depth = np.ascontiguousarray(full[r0:r0 + h, c0:c0 + w])
-    img = gen.make_image(h, w, c, seed)
-    return pm, gen.make_unprojection(pm), depth, img
 
 
 def test_lifted_pixels_project_back_onto_themselves():
