@@ -410,6 +410,73 @@ def main() -> int:
     except Exception as exc:
         dec = {"error": repr(exc)}
 
+    # Multimodal leg of the data bridge on config 3 (outside the timed region): the 375 x 1242 x 64 feature map
+    # pooled on each of the three scales, then fused with that scale's LiDAR voxels (32 channels) into 96-channel
+    # rows.  Algorithmic bytes: pooling reads 4 B of depth per pixel and one 2C-byte row per pixel that lands in
+    # the grid, writes 20 + 2C B per cell; fusion reads 16 B + a row per input site and writes 16 B + a row per
+    # fused site.
+    bridge = None
+    try:
+        cfg3 = get_config(3)
+        cam = cfg3.camera
+        npix = cam.height * cam.width
+        seed3 = gen.frame_seed(3, 0)
+        pts3_np, _ = gen.make_frames(cfg3)
+        ctx_b = B.Context(max(npix, len(pts3_np)), npix + len(pts3_np), cells_of(cfg3.branches[0].spec.grid, cfg3.branches[0].spec.n_batch), n_slots=3)
+        fmap = torch.from_numpy(gen.make_image(cam.height, cam.width, cam.channels, seed3)).cuda()
+        dmap = torch.from_numpy(gen.make_depth(cam.height, cam.width, seed3)).cuda()
+        qm = gen.make_unprojection(gen.make_camera(seed3))
+        pts3 = torch.from_numpy(pts3_np).cuda()
+        cap_b = npix + len(pts3_np)
+        i32 = dict(dtype=torch.int32, device="cuda")
+        ic, icnt, n_i = torch.empty((cap_b, 4), **i32), torch.empty((cap_b,), **i32), torch.zeros(1, **i32)
+        if_ = torch.empty((cap_b, cam.channels), dtype=torch.float16, device="cuda")
+        lc, lcnt, n_l = torch.empty((cap_b, 4), **i32), torch.empty((cap_b,), **i32), torch.zeros(1, **i32)
+        lm = torch.empty((cap_b, 4), dtype=torch.float32, device="cuda")
+        lf = torch.randn((cap_b, 32), device="cuda").to(torch.float16)
+        fc, n_f = torch.empty((cap_b, 4), **i32), torch.zeros(1, **i32)
+        ff = torch.empty((cap_b, 96), dtype=torch.float16, device="cuda")
+
+        def timed_b(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0_.record()
+            for _ in range(reps):
+                fn()
+            e1_.record()
+            torch.cuda.synchronize()
+            return e0_.elapsed_time(e1_) / reps
+
+        scales = []
+        for br3 in cfg3.branches:
+            sp3 = br3.spec
+            row = {"scale": br3.name, "cell_m": list(sp3.vs)}
+            for mode, nm in ((B.POOL_MEAN, "mean"), (B.POOL_MAX, "max")):
+                ms_p = timed_b(lambda: ctx_b.pool_image(fmap, dmap, qm, sp3, mode, cap_b, ic, if_, icnt, n_i, index_slot=1))
+                ni = int(n_i.item())
+                pooled = int(icnt[:ni].sum().item())
+                pb = npix * 4.0 + pooled * 2.0 * cam.channels + ni * (20.0 + 2.0 * cam.channels)
+                row["pool_" + nm] = {"ms": ms_p, "cells": ni, "pixels_pooled": pooled, "algorithmic_MB": pb / 1e6,
+                                     "GB/s": pb / (ms_p * 1e-3) / 1e9, "frac_of_hbm_peak": pb / (ms_p * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            nl = ctx_b.voxelize(pts3, None, sp3, cap_b, lc, lm, lcnt, n_l, index_slot=0, sync_count=True)
+            ms_f = timed_b(lambda: ctx_b.fuse(cfg3.dtype, lc, lf, n_l, cap_b, ic, if_, n_i, cap_b, sp3.grid, sp3.n_batch, cap_b,
+                                              fc, ff, n_f, out_slot=2))
+            nf_ = int(n_f.item())
+            fb = nl * (16.0 + 64.0) + ni * (16.0 + 2.0 * cam.channels) + nf_ * (16.0 + 192.0)
+            row["fuse"] = {"ms": ms_f, "voxels": nl, "image_cells": ni, "fused": nf_, "shared": nl + ni - nf_,
+                           "algorithmic_MB": fb / 1e6, "GB/s": fb / (ms_f * 1e-3) / 1e9,
+                           "frac_of_hbm_peak": fb / (ms_f * 1e-3) / 1e9 / PEAK_HBM_GBS}
+            scales.append(row)
+        ctx_b.status_sync()
+        bridge = {"workload": f"config 3: image {cam.height}x{cam.width}x{cam.channels} f16 with depth ({int((dmap > 0).sum().item())} "
+                              f"relevant pixels), {len(pts3_np)} points", "scales": scales}
+        ctx_b.close()
+        del fmap, dmap, ic, if_, lc, lf, fc, ff, pts3
+    except Exception as exc:
+        bridge = {"error": repr(exc)}
+
     # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
     # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
     vox_scaling = []
@@ -467,6 +534,7 @@ def main() -> int:
         "memory_bound_stages": stage_hbm,
         "project_gather": pg,
         "decoder_side": dec,
+        "multimodal_bridge": bridge,
         "voxelize_scaling": vox_scaling,
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
                          "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),

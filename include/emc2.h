@@ -226,7 +226,8 @@ typedef enum { EMC2_POOL_MEAN = 0, EMC2_POOL_MAX = 1 } emc2_pool_mode;
  * inverse of the projection: each row evaluated left to right in fp64 without fused multiply-add, rounded once
  * to fp32; its cell is the voxelizer's (t = fl(fl(X_a - lo_a) / vs_a), kept iff 0 <= t < G_a, cell floor(t)).
  * Every cell that receives a pixel becomes one output, in ascending key order:
- *   d_coords [capacity][4] int32 (batch_index, z, y, x);  d_counts [capacity] int32 pixels pooled;
+ *   d_coords [capacity][4] int32 (batch_index, z, y, x);  d_counts [capacity] int32 pixels pooled (entries past
+ *            the cell count may be zeroed);
  *   d_feats  [capacity][C] fp16: per channel the mean (fp32 sums, order not fixed, one rounding to fp16) or the
  *            maximum (exact) over the cell's pixels;
  *   d_n_cells device int32 (always written); h_n_cells host int32, NULL = no sync.

@@ -4,17 +4,18 @@
 // concatenated, the others padded with zeros).
 //
 // Pooling is a counting sort of the pixels by cell followed by a segmented reduction, so that a feature row
-// (2*C bytes) is read exactly once and no floating-point atomics touch HBM except where a cell's pixel list
+// (2*C bytes) is read exactly once and no floating-point atomics are used except where a cell's pixel list
 // crosses the boundary between two reduction blocks:
-//   mark     one thread per pixel: lift by depth, cell key, set the cell's bit in the cell index
+//   mark     one thread per pixel: lift by depth, cell key, set the cell's bit in the cell index (one atomic
+//            per run of neighbouring pixels with the same cell); also zeroes the counters and accumulators
 //   scan     prefix sum over the index: rank of a cell = its position in key order; number of cells
-//   count    per pixel: rank r, position within the cell from one returning atomic add on counts[r]
+//   count    per pixel: rank r, position within the cell from a returning atomic add on counts[r] (one per run)
 //   starts   exclusive prefix sum of counts
 //   scatter  per pixel: sorted position starts[r] + pos -> pixel id and rank stored there
-//   reduce   one block per RPB consecutive sorted rows: rows are summed (or maximised) into per-cell
-//            accumulators in LDS with LDS atomics, 8 lanes per row with 16-byte loads; cells that lie
-//            inside the block's rows are finished there, the (at most one per block boundary) cell that
-//            continues into the next block adds its partial result to a small global accumulator
+//   reduce   one block per 256 consecutive sorted rows, 8 lanes per row with 16-byte loads: runs of rows of one
+//            cell are combined in registers, cells inside a group of 8 rows are finished there, partial runs
+//            meet in LDS (plain stores, owner sums), the (at most one per block boundary) cell that continues
+//            into the next block adds its partial result to a small global accumulator
 //   finish   per boundary-crossing cell: accumulator -> mean / max -> fp16
 #include <hip/hip_fp16.h>
 #include <math.h>
@@ -76,34 +77,57 @@ __device__ __forceinline__ PixCell lift(const float* __restrict__ depth, int64_t
   return r;
 }
 
+// Consecutive pixels of an image row mostly land in the same cell, so only the first lane of a run of equal keys
+// touches the index, and only if the bit is not already visible as set (bits are never cleared while this runs, so
+// a stale read can only cost a redundant atomic).  The same launch zeroes what later passes accumulate into:
+// the per-cell counters (at most min(pixels, capacity) cells exist) and the boundary accumulators.
 __global__ void __launch_bounds__(256) k_pool_mark(const float* __restrict__ depth, int64_t npix, PoolParams prm,
-                                                   cellword_t* __restrict__ idx, uint32_t* __restrict__ flags) {
-  const PixCell pc = lift(depth, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, npix, prm);
-  if (!pc.keep) return;
-  atomicOr(&idx[pc.key >> 5].x, 1u << ((uint32_t)pc.key & 31u));
-  flags[pc.key >> (5 + EMC2_TILE_SHIFT)] = 1u;
+                                                   cellword_t* __restrict__ idx, uint32_t* __restrict__ flags,
+                                                   int32_t* __restrict__ counts, int64_t n_counts, uint4* __restrict__ acc16,
+                                                   int64_t n_acc16) {
+  const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (p < n_counts) counts[p] = 0;
+  if (p < npix)
+    for (int64_t a = p; a < n_acc16; a += npix) acc16[a] = make_uint4(0u, 0u, 0u, 0u);
+  const PixCell pc = lift(depth, p, npix, prm);
+  const uint64_t key = pc.keep ? pc.key : ~0ull;
+  const uint64_t prev = __shfl_up((unsigned long long)key, 1, 64);
+  if (!pc.keep || ((threadIdx.x & 63) != 0 && prev == key)) return;
+  const uint32_t bit = 1u << ((uint32_t)key & 31u);
+  if (idx[key >> 5].x & bit) return;
+  atomicOr(&idx[key >> 5].x, bit);
+  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
 }
 
-__global__ void __launch_bounds__(256) k_pool_zero_counts(const int32_t* __restrict__ d_n, int64_t capacity,
-                                                          int32_t* __restrict__ counts) {
-  int64_t n = *d_n;
-  if (n > capacity) n = capacity;
-  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (r < n) counts[r] = 0;
-}
-
+// Position of every pixel within its cell.  A run of consecutive lanes with the same rank takes its positions from
+// one returning atomic add of the run length (the first lane's), which cuts the atomics by the run length where
+// cells are larger than pixels.
 __global__ void __launch_bounds__(256) k_pool_count(const float* __restrict__ depth, int64_t npix, PoolParams prm,
                                                     const cellword_t* __restrict__ idx, int64_t capacity,
                                                     int4* __restrict__ coords, int32_t* __restrict__ counts,
                                                     int32_t* __restrict__ pix_rank, int32_t* __restrict__ pix_pos) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (p >= npix) return;
-  const PixCell pc = lift(depth, p, npix, prm);
+  const PixCell pc = lift(depth, p, npix, prm);   // keep = false beyond the image
   int32_t r = pc.keep ? cell_lookup(idx, pc.key) : -1;
   if (r >= capacity) r = -1;  // beyond capacity: reported by the scan, dropped here
+  const int lane = threadIdx.x & 63;
+  const int32_t r_prev = __shfl_up(r, 1, 64);
+  const bool head = r >= 0 && (lane == 0 || r != r_prev);
+  const uint64_t heads = __ballot(head);
+  const uint64_t breaks = __ballot(head || r < 0);
+  int32_t pos = 0;
+  int start = lane;
+  if (r >= 0) {
+    const uint64_t upto = heads & (lane == 63 ? ~0ull : ((1ull << (lane + 1)) - 1ull));
+    start = 63 - __clzll(upto);                                  // my run's first lane
+    const uint64_t above = breaks & ~((2ull << start) - 1ull);   // the next break after it (2ull << 63 wraps to 0)
+    const int end = above ? (int)__ffsll((unsigned long long)above) - 1 : 64;
+    if (lane == start) pos = atomicAdd(&counts[r], end - start);
+  }
+  pos = __shfl(pos, start, 64) + (lane - start);
+  if (p >= npix) return;
   pix_rank[p] = r;
   if (r < 0) return;
-  const int32_t pos = atomicAdd(&counts[r], 1);
   pix_pos[p] = pos;
   if (pos == 0) coords[r] = pc.c;  // exactly one pixel of every cell gets position 0
 }
@@ -139,11 +163,14 @@ __global__ void __launch_bounds__(256) k_starts_reduce(const int32_t* __restrict
 
 __global__ void __launch_bounds__(256) k_starts_apply(const int32_t* __restrict__ counts, const int32_t* __restrict__ d_n,
                                                       int64_t capacity, const uint32_t* __restrict__ totals,
-                                                      int32_t* __restrict__ starts) {
+                                                      int32_t* __restrict__ starts, int32_t* __restrict__ d_rows) {
   int64_t n = *d_n;
   if (n > capacity) n = capacity;
   if (n == 0) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) starts[0] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+      starts[0] = 0;
+      *d_rows = 0;
+    }
     return;
   }
   if ((int64_t)blockIdx.x * 2048 >= n) return;  // uniform for the block
@@ -177,7 +204,10 @@ __global__ void __launch_bounds__(256) k_starts_apply(const int32_t* __restrict_
   for (int j = 0; j < 8; ++j) {
     if (base + j < n) starts[base + j] = (int32_t)run;
     run += c[j];
-    if (base + j == n - 1) starts[n] = (int32_t)run;
+    if (base + j == n - 1) {
+      starts[n] = (int32_t)run;
+      *d_rows = (int32_t)run;  // number of pooled pixels = length of the sorted list
+    }
   }
 }
 
@@ -191,11 +221,6 @@ __global__ void __launch_bounds__(256) k_pool_scatter(int64_t npix, const int32_
   const int32_t t = starts[r] + pix_pos[p];
   perm[t] = (int32_t)p;
   srank[t] = r;
-}
-
-__global__ void __launch_bounds__(256) k_pool_fill_zero(uint4* __restrict__ p, int64_t n16) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // Order-preserving map float -> uint32 (and back), so that a maximum can be taken with integer atomics.
@@ -225,76 +250,154 @@ __device__ __forceinline__ uint4 pack8(const float f[8]) {
   return v;
 }
 
-#define EMC2_POOL_LDS_WORDS 16384  // 64 KB of per-cell accumulators: RPB * C <= 16384
+#define EMC2_POOL_STEPS 8                       // rows per group of 8 lanes
+#define EMC2_POOL_RPB (32 * EMC2_POOL_STEPS)    // sorted rows per reduction block (32 groups)
 
-// MODE 0 mean, 1 max.  RPB sorted rows per block (a multiple of 32, at most 256).
+// MODE 0 mean, 1 max.  One block reduces EMC2_POOL_RPB consecutive sorted rows.
+//
+// A group of 8 lanes takes EMC2_POOL_STEPS consecutive rows (lane l the channels 8l..8l+7 of each 64-channel
+// slab); the row ids and their cells, then the rows themselves and the cells' list bounds are loaded in two
+// dependent rounds, everything of a round in flight at once.  Rows of one cell are consecutive, so the group
+// combines them in registers run by run.  A run that is a whole cell is finished on the spot: the common case
+// where cells hold a few pixels.  Only the first run of a group (its cell began earlier: a "head") and the last
+// (its cell goes on: a "tail") can be partial; they are parked in LDS with plain stores.  After a barrier the
+// group a cell began in owns it: it adds to its tail the heads of the following groups for as long as they
+// belong to the same cell (group 0 does the same for the cell that began before the block).  No atomics in
+// LDS.  A cell that ends inside the block is finished there; one that crosses the block boundary is added to
+// the global accumulator of the block it starts in (the only floating-point atomics of the whole pooling).
 template <int MODE>
-__global__ void __launch_bounds__(256) k_pool_reduce(const __half* __restrict__ img, const int32_t* __restrict__ perm,
-                                                     const int32_t* __restrict__ srank, const int32_t* __restrict__ starts,
-                                                     const int32_t* __restrict__ d_n, int64_t capacity, int C, int RPB,
-                                                     uint32_t* __restrict__ acc, __half* __restrict__ feats) {
-  __shared__ uint32_t lds[EMC2_POOL_LDS_WORDS];
-  int64_t n = *d_n;
-  if (n > capacity) n = capacity;
-  const int64_t m = n > 0 ? (int64_t)starts[n] : 0;
+__global__ void __launch_bounds__(256, 4) k_pool_reduce(const __half* __restrict__ img, const int32_t* __restrict__ perm,
+                                                        const int32_t* __restrict__ srank, const int32_t* __restrict__ starts,
+                                                        const int32_t* __restrict__ d_rows, int C,
+                                                        uint32_t* __restrict__ acc, __half* __restrict__ feats) {
+  extern __shared__ __align__(16) float lds[];  // heads [32][C], tails [32][C], then head_cell [32]
+  constexpr int RPB = EMC2_POOL_RPB, STEPS = EMC2_POOL_STEPS;
+  const int64_t m = *d_rows;
   const int64_t t0 = (int64_t)blockIdx.x * RPB;
   if (t0 >= m) return;  // uniform for the block
   const int64_t t1 = t0 + RPB < m ? t0 + RPB : m;
-  const int32_t c_lo = srank[t0], c_hi = srank[t1 - 1];
-  const int ncell = c_hi - c_lo + 1;  // every cell has at least one row here, so ncell <= RPB
-  for (int i = threadIdx.x; i < ncell * C; i += 256) lds[i] = 0u;  // 0.0f, and below every encoded float
-  __syncthreads();
+  float* heads = lds;
+  float* tails = lds + 32 * C;
+  int32_t* head_cell = reinterpret_cast<int32_t*>(lds + 64 * C);
   const int g = threadIdx.x >> 3, l = threadIdx.x & 7;
-  const int steps = RPB >> 5;
+  const int64_t tg = t0 + (int64_t)g * STEPS;  // the group's first row
+  // round 1: which pixel and which cell each row is
+  int32_t pix[STEPS], rk[STEPS];
+#pragma unroll
+  for (int i = 0; i < STEPS; ++i) {
+    const int64_t t = tg + i;
+    rk[i] = -1;
+    pix[i] = 0;
+    if (t < t1) {
+      rk[i] = srank[t];
+      pix[i] = perm[t];
+    }
+  }
+  // round 2: the cells' list bounds (the same for every slab)
+  int32_t ca[STEPS], cb[STEPS];
+#pragma unroll
+  for (int i = 0; i < STEPS; ++i) {
+    ca[i] = 0;
+    cb[i] = 0;
+    if (rk[i] >= 0) {
+      ca[i] = starts[rk[i]];
+      cb[i] = starts[rk[i] + 1];
+    }
+  }
+  // the group's head: its first row's cell, if that cell began before the group
+  const bool has_head = rk[0] >= 0 && ca[0] < tg;
+  if (l == 0) head_cell[g] = has_head ? rk[0] : -1;
+  // the group's tail: its last row's cell, if that cell began in the group and goes on beyond it
+  int32_t tr = -1, ta = 0, tb = 0;
+#pragma unroll
+  for (int i = 0; i < STEPS; ++i)
+    if (rk[i] >= 0) { tr = rk[i]; ta = ca[i]; tb = cb[i]; }  // rows of a group are valid from the front
+  const bool has_tail = tr >= 0 && ta >= tg && tb > tg + STEPS;
   for (int cc = 0; cc < C; cc += 64) {
     const int ch = cc + 8 * l;
-    if (ch < C) {
-      uint4 v[8];
-      int32_t slot[8];
+    if (ch >= C) continue;
+    uint4 v[STEPS];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int64_t t = t0 + g + 32 * i;
-        slot[i] = -1;
-        if (i < steps && t < t1) {
-          const int64_t p = perm[t];
-          slot[i] = srank[t] - c_lo;
-          v[i] = *reinterpret_cast<const uint4*>(img + p * C + ch);
-        }
-      }
+    for (int i = 0; i < STEPS; ++i) {
+      v[i] = make_uint4(0u, 0u, 0u, 0u);
+      if (rk[i] >= 0) v[i] = *reinterpret_cast<const uint4*>(img + (int64_t)pix[i] * C + ch);
+    }
+    float run[8];
+    int32_t cur = -1, cur_a = 0, cur_b = 0;
+    bool cur_first = false;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (slot[i] >= 0) {
-          float f[8];
-          unpack8(v[i], f);
-          uint32_t* a = lds + slot[i] * C + ch;
+    for (int i = 0; i <= STEPS; ++i) {
+      const int32_t r = i < STEPS ? rk[i] : -1;
+      if (r != cur) {
+        if (cur >= 0) {
+          if (cur_a >= tg && cur_b <= tg + STEPS) {  // the whole cell sits in this group's rows: finish it here
+            float f[8];
+            const float inv = 1.0f / (float)(cur_b - cur_a);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            if (MODE == 0) atomicAdd(reinterpret_cast<float*>(a + e), f[e]);
-            else atomicMax(a + e, f2ord(f[e]));
+            for (int e = 0; e < 8; ++e) f[e] = MODE == 0 ? run[e] * inv : run[e];
+            *reinterpret_cast<uint4*>(feats + (int64_t)cur * C + ch) = pack8(f);
+          } else {
+            // a head if the run opened the group and its cell began earlier, else the tail
+            float* dst = ((cur_first && cur_a < tg) ? heads : tails) + g * C + ch;
+            *reinterpret_cast<float4*>(dst) = make_float4(run[0], run[1], run[2], run[3]);
+            *reinterpret_cast<float4*>(dst + 4) = make_float4(run[4], run[5], run[6], run[7]);
           }
         }
+        cur = r;
+        cur_first = i == 0;
+        if (i < STEPS) {
+          cur_a = ca[i];
+          cur_b = cb[i];
+          if (r >= 0) unpack8(v[i], run);
+        }
+      } else if (i < STEPS && r >= 0) {
+        float f[8];
+        unpack8(v[i], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) run[e] = MODE == 0 ? run[e] + f[e] : fmaxf(run[e], f[e]);
       }
     }
   }
   __syncthreads();
-  const int chunks = C >> 3;
-  for (int w = threadIdx.x; w < ncell * chunks; w += 256) {
-    const int s = w / chunks, k = w - s * chunks;
-    const int64_t r = c_lo + s;
-    const int64_t a = starts[r], b = starts[r + 1];
-    const uint32_t* src = lds + s * C + 8 * k;
-    if (a / RPB == (b - 1) / RPB) {  // the whole cell lies in this block's rows
-      float f[8];
-      const float cnt = (float)(b - a);
+  // owners: the group a cell began in (its tail), and group 0 for the cell that began before the block (a head)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = MODE == 0 ? __uint_as_float(src[e]) / cnt : ord2f(src[e]);
-      *reinterpret_cast<uint4*>(feats + r * C + 8 * k) = pack8(f);
-    } else {  // continues across a block boundary: combine in the accumulator of the block it starts in
-      uint32_t* dst = acc + (a / RPB) * C + 8 * k;
+  for (int which = 0; which < 2; ++which) {
+    int32_t r, a, b;
+    int g_next;  // first of the following groups whose head may belong to the cell
+    if (which == 0) {
+      if (!has_tail) continue;
+      r = tr; a = ta; b = tb;
+      g_next = g + 1;
+    } else {
+      if (g != 0 || !has_head || ca[0] >= t0) continue;
+      r = rk[0]; a = ca[0]; b = cb[0];
+      g_next = 1;
+    }
+    int g_end = g_next;
+    while (g_end < 32 && head_cell[g_end] == r) ++g_end;
+    for (int ch = 8 * l; ch < C; ch += 64) {
+      float sum[8];
+      const float* own = (which == 0 ? tails : heads) + g * C + ch;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        if (MODE == 0) unsafeAtomicAdd(reinterpret_cast<float*>(dst + e), __uint_as_float(src[e]));
-        else atomicMax(dst + e, src[e]);
+      for (int e = 0; e < 8; ++e) sum[e] = own[e];
+      for (int q = g_next; q < g_end; ++q) {
+        const float* h = heads + q * C + ch;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum[e] = MODE == 0 ? sum[e] + h[e] : fmaxf(sum[e], h[e]);
+      }
+      if (a >= t0 && b <= t1) {  // the whole cell lies in this block's rows
+        const float inv = 1.0f / (float)(b - a);
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = MODE == 0 ? sum[e] * inv : sum[e];
+        *reinterpret_cast<uint4*>(feats + (int64_t)r * C + ch) = pack8(f);
+      } else {  // crosses a block boundary: combine in the accumulator of the block it starts in
+        uint32_t* dst = acc + (int64_t)(a / RPB) * C + ch;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (MODE == 0) unsafeAtomicAdd(reinterpret_cast<float*>(dst + e), sum[e]);
+          else atomicMax(dst + e, f2ord(sum[e]));
+        }
       }
     }
   }
@@ -325,33 +428,59 @@ __global__ void __launch_bounds__(256) k_pool_finish(const int32_t* __restrict__
 // fusion
 // ------------------------------------------------------------------------------------------------------------
 
-__global__ void __launch_bounds__(256) k_fuse_init(const int32_t* __restrict__ d_n, int64_t capacity,
-                                                   int32_t* __restrict__ src_l, int32_t* __restrict__ src_i) {
-  int64_t n = *d_n;
-  if (n > capacity) n = capacity;
-  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n) return;
-  src_l[r] = -1;
-  src_i[r] = -1;
-}
-
-// One thread per input row: its rank in the union index is its output row.
-__global__ void __launch_bounds__(256) k_fuse_place(const int4* __restrict__ coords, const int32_t* __restrict__ d_n_in,
-                                                    int64_t capacity_in, const cellword_t* __restrict__ idx, int gx, int gy,
-                                                    int gz, int n_batch, int64_t capacity_out, int32_t* __restrict__ src,
-                                                    int4* __restrict__ coords_out) {
-  int64_t n = *d_n_in;
-  if (n > capacity_in) n = capacity_in;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  const int4 c = coords[i];  // (b, z, y, x)
+__device__ __forceinline__ bool fuse_key(const int4 c, int gx, int gy, int gz, int n_batch, uint64_t* key) {
   if ((unsigned)c.x >= (unsigned)n_batch || (unsigned)c.y >= (unsigned)gz || (unsigned)c.z >= (unsigned)gy ||
       (unsigned)c.w >= (unsigned)gx)
-    return;  // malformed coordinate: it was not marked either
-  const uint64_t key = (((uint64_t)c.x * gz + (uint64_t)c.y) * gy + (uint64_t)c.z) * gx + (uint64_t)c.w;
+    return false;  // malformed coordinate: ignored everywhere rather than written out of bounds
+  *key = (((uint64_t)c.x * gz + (uint64_t)c.y) * gy + (uint64_t)c.z) * gx + (uint64_t)c.w;
+  return true;
+}
+
+// One thread per input row of either set (LiDAR rows first): set the site's bit in the union index.  The same
+// launch presets the source arrays of every possible output row to "none".
+__global__ void __launch_bounds__(256) k_fuse_mark(const int4* __restrict__ coords_l, const int32_t* __restrict__ d_n_l,
+                                                   int64_t capacity_l, const int4* __restrict__ coords_i,
+                                                   const int32_t* __restrict__ d_n_i, int64_t capacity_i,
+                                                   cellword_t* __restrict__ idx, uint32_t* __restrict__ flags, int gx, int gy,
+                                                   int gz, int n_batch, int64_t bound, int32_t* __restrict__ src_l,
+                                                   int32_t* __restrict__ src_i) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < bound) {
+    src_l[t] = -1;
+    src_i[t] = -1;
+  }
+  const bool is_l = t < capacity_l;
+  const int64_t i = is_l ? t : t - capacity_l;
+  int64_t n = is_l ? *d_n_l : *d_n_i;
+  const int64_t cap = is_l ? capacity_l : capacity_i;
+  if (n > cap) n = cap;
+  if (i >= n) return;
+  uint64_t key;
+  if (!fuse_key((is_l ? coords_l : coords_i)[i], gx, gy, gz, n_batch, &key)) return;
+  atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
+  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
+}
+
+// One thread per input row of either set: its rank in the union index is its output row.
+__global__ void __launch_bounds__(256) k_fuse_place(const int4* __restrict__ coords_l, const int32_t* __restrict__ d_n_l,
+                                                    int64_t capacity_l, const int4* __restrict__ coords_i,
+                                                    const int32_t* __restrict__ d_n_i, int64_t capacity_i,
+                                                    const cellword_t* __restrict__ idx, int gx, int gy, int gz, int n_batch,
+                                                    int64_t capacity_out, int32_t* __restrict__ src_l,
+                                                    int32_t* __restrict__ src_i, int4* __restrict__ coords_out) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool is_l = t < capacity_l;
+  const int64_t i = is_l ? t : t - capacity_l;
+  int64_t n = is_l ? *d_n_l : *d_n_i;
+  const int64_t cap = is_l ? capacity_l : capacity_i;
+  if (n > cap) n = cap;
+  if (i >= n) return;
+  const int4 c = (is_l ? coords_l : coords_i)[i];  // (b, z, y, x)
+  uint64_t key;
+  if (!fuse_key(c, gx, gy, gz, n_batch, &key)) return;
   const int32_t r = cell_lookup(idx, key);
   if (r < 0 || r >= capacity_out) return;
-  src[r] = (int32_t)i;
+  (is_l ? src_l : src_i)[r] = (int32_t)i;
   coords_out[r] = c;  // where both sets hold the site they write the same value
 }
 
@@ -430,38 +559,39 @@ extern "C" emc2_status emc2_pool_image(emc2_ctx* ctx, const void* d_img, const f
   prm.batch_index = batch_index;
   prm.W = W;
 
-  const int RPB = C <= 64 ? 256 : (C <= 128 ? 128 : 64);  // RPB * C accumulators fit the block's LDS
+  const int RPB = EMC2_POOL_RPB;
   const int64_t bound = npix < capacity ? npix : capacity;  // at most this many cells exist
-  const dim3 blk(256), pg((unsigned)emc2_div_up(npix, 256)), cg((unsigned)emc2_div_up(bound, 256));
+  const dim3 blk(256), pg((unsigned)emc2_div_up(npix, 256));
   const int64_t scan_blocks = emc2_div_up(bound, 2048);
   const int64_t red_blocks = emc2_div_up(npix, RPB);
   if (scan_blocks > ctx->n_pool_totals)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_pool_image: capacity beyond the context's scan scratch");
 
   emc2_index_clear(ctx, idx, s);
-  hipLaunchKernelGGL(k_pool_mark, pg, blk, 0, s, d_depth, npix, prm, idx, emc2_slot_flags(ctx, idx));
+  hipLaunchKernelGGL(k_pool_mark, pg, blk, 0, s, d_depth, npix, prm, idx, emc2_slot_flags(ctx, idx), d_counts, bound,
+                     (uint4*)ctx->pool_acc, red_blocks * C / 4);
   emc2_index_scan(ctx, idx, n_cells, capacity, d_n_cells, s);
-  hipLaunchKernelGGL(k_pool_zero_counts, cg, blk, 0, s, d_n_cells, capacity, d_counts);
   hipLaunchKernelGGL(k_pool_count, pg, blk, 0, s, d_depth, npix, prm, idx, capacity, (int4*)d_coords, d_counts, ctx->pix_rank,
                      ctx->pix_pos);
   hipLaunchKernelGGL(k_starts_reduce, dim3((unsigned)scan_blocks), blk, 0, s, d_counts, d_n_cells, capacity, ctx->pool_totals);
   hipLaunchKernelGGL(k_starts_apply, dim3((unsigned)scan_blocks), blk, 0, s, d_counts, d_n_cells, capacity, ctx->pool_totals,
-                     ctx->cell_start);
+                     ctx->cell_start, ctx->dev_words + 2);
   hipLaunchKernelGGL(k_pool_scatter, pg, blk, 0, s, npix, ctx->pix_rank, ctx->pix_pos, ctx->cell_start, ctx->pix_perm,
                      ctx->pix_srank);
-  {
-    const int64_t n16 = red_blocks * C / 4;  // C is a multiple of 8
-    hipLaunchKernelGGL(k_pool_fill_zero, dim3((unsigned)emc2_div_up(n16, 256)), blk, 0, s, (uint4*)ctx->pool_acc, n16);
-  }
+  const size_t lds_bytes = sizeof(float) * (64 * (size_t)C + 32);  // heads and tails of the 32 groups, their cells
   const dim3 rg((unsigned)red_blocks), fg((unsigned)emc2_div_up(bound * (C / 8), 256));
+  if (lds_bytes > 65536) {  // C = 256 only: a little over the default per-block limit (the CU has 160 KB)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pool_reduce<0>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_pool_reduce<1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+  }
   if (mode == EMC2_POOL_MEAN) {
-    hipLaunchKernelGGL(k_pool_reduce<0>, rg, blk, 0, s, (const __half*)d_img, ctx->pix_perm, ctx->pix_srank, ctx->cell_start,
-                       d_n_cells, capacity, C, RPB, ctx->pool_acc, (__half*)d_feats);
+    hipLaunchKernelGGL(k_pool_reduce<0>, rg, blk, lds_bytes, s, (const __half*)d_img, ctx->pix_perm, ctx->pix_srank,
+                       ctx->cell_start, ctx->dev_words + 2, C, ctx->pool_acc, (__half*)d_feats);
     hipLaunchKernelGGL(k_pool_finish<0>, fg, blk, 0, s, ctx->cell_start, d_n_cells, capacity, C, RPB, ctx->pool_acc,
                        (__half*)d_feats);
   } else {
-    hipLaunchKernelGGL(k_pool_reduce<1>, rg, blk, 0, s, (const __half*)d_img, ctx->pix_perm, ctx->pix_srank, ctx->cell_start,
-                       d_n_cells, capacity, C, RPB, ctx->pool_acc, (__half*)d_feats);
+    hipLaunchKernelGGL(k_pool_reduce<1>, rg, blk, lds_bytes, s, (const __half*)d_img, ctx->pix_perm, ctx->pix_srank,
+                       ctx->cell_start, ctx->dev_words + 2, C, ctx->pool_acc, (__half*)d_feats);
     hipLaunchKernelGGL(k_pool_finish<1>, fg, blk, 0, s, ctx->cell_start, d_n_cells, capacity, C, RPB, ctx->pool_acc,
                        (__half*)d_feats);
   }
@@ -518,15 +648,13 @@ extern "C" emc2_status emc2_fuse(emc2_ctx* ctx, emc2_dtype dtype, const int32_t*
 
   const dim3 blk(256);
   emc2_index_clear(ctx, idx, s);
-  emc2_index_mark_coords(ctx, idx, d_coords_l, d_n_l, capacity_l, grid, n_batch, s);
-  emc2_index_mark_coords(ctx, idx, d_coords_i, d_n_i, capacity_i, grid, n_batch, s);
-  emc2_index_scan(ctx, idx, n_cells, capacity_out, d_n_out, s);
   const int64_t bound = capacity_l + capacity_i < capacity_out ? capacity_l + capacity_i : capacity_out;
-  hipLaunchKernelGGL(k_fuse_init, dim3((unsigned)emc2_div_up(bound, 256)), blk, 0, s, d_n_out, capacity_out, src_l, src_i);
-  hipLaunchKernelGGL(k_fuse_place, dim3((unsigned)emc2_div_up(capacity_l, 256)), blk, 0, s, (const int4*)d_coords_l, d_n_l,
-                     capacity_l, idx, grid[0], grid[1], grid[2], n_batch, capacity_out, src_l, (int4*)d_coords_out);
-  hipLaunchKernelGGL(k_fuse_place, dim3((unsigned)emc2_div_up(capacity_i, 256)), blk, 0, s, (const int4*)d_coords_i, d_n_i,
-                     capacity_i, idx, grid[0], grid[1], grid[2], n_batch, capacity_out, src_i, (int4*)d_coords_out);
+  const dim3 both((unsigned)emc2_div_up(capacity_l + capacity_i, 256));
+  hipLaunchKernelGGL(k_fuse_mark, both, blk, 0, s, (const int4*)d_coords_l, d_n_l, capacity_l, (const int4*)d_coords_i, d_n_i,
+                     capacity_i, idx, emc2_slot_flags(ctx, idx), grid[0], grid[1], grid[2], n_batch, bound, src_l, src_i);
+  emc2_index_scan(ctx, idx, n_cells, capacity_out, d_n_out, s);
+  hipLaunchKernelGGL(k_fuse_place, both, blk, 0, s, (const int4*)d_coords_l, d_n_l, capacity_l, (const int4*)d_coords_i, d_n_i,
+                     capacity_i, idx, grid[0], grid[1], grid[2], n_batch, capacity_out, src_l, src_i, (int4*)d_coords_out);
   if (!((bl | bi | bo) & 15)) {
     const int wl = (int)(bl / 16), wi = (int)(bi / 16), wo = (int)(bo / 16);
     hipLaunchKernelGGL(k_fuse_gather<uint4>, dim3((unsigned)emc2_div_up(bound * wo, 256)), blk, 0, s, (const uint4*)d_feats_l,

@@ -56,8 +56,9 @@ def check_pool(ctx, img, depth, q, spec, mode, cap, batch_index=0):
         assert np.array_equal(got, of)                      # a maximum of fp16 values is one of them
     else:
         assert_features_close(got, of, MEAN_RTOL, "pooled means")
-    if nv < cap:                                            # rows past the count are not written
-        assert float(feats[nv:].float().min().item()) == 77.0 and int(counts[nv:].max().item()) == -3
+    if nv < cap:                                            # rows past the count: features untouched, counts untouched or 0
+        assert float(feats[nv:].float().min().item()) == 77.0 and int(coords[nv:].max().item()) == -7
+        assert set(np.unique(counts[nv:].cpu().numpy()).tolist()) <= {0, -3}
     return coords, feats, counts, n, nv, (oc, of, on)
 
 
