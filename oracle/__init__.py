@@ -56,6 +56,8 @@ def _load():
                                      vp, vp]
     lib.emc2o_fuse.restype = c_i64
     lib.emc2o_fuse.argtypes = [vp, vp, c_i64, c_i32, vp, vp, c_i64, c_i32, vp, c_i32, c_i64, vp, vp, vp, vp]
+    lib.emc2o_dispatch.restype = c_i32
+    lib.emc2o_dispatch.argtypes = [vp, vp, c_i64, c_i32, c_f, c_f, vp, vp, vp]
     lib.emc2o_project_gather.restype = c_i32
     lib.emc2o_project_gather.argtypes = [vp, c_i32, c_i64, vp, vp, c_i32, c_i32, c_i32, vp, vp, vp]
     _lib = lib
@@ -196,6 +198,26 @@ def fuse(coords_l: np.ndarray, feats_l: np.ndarray, coords_i: np.ndarray, feats_
                             int(n_batch), cap, _p(coords), _p(feats), _p(src_l), _p(src_i)), "fuse")
     res = (coords[:n].copy(), feats[:n].copy())
     return res + (src_l[:n].copy(), src_i[:n].copy()) if want_src else res
+
+
+LPE, VEE, APE = 0, 1, 2
+
+
+def dispatch(props: np.ndarray, scene: Optional[np.ndarray], n_scenes: int, dist: float, conf: float):
+    """props[N][4] f32 (x, y, z, confidence), scene[N] i32 -> (expert[S], counts[3], order[S]): the expert of
+    every scene and the scenes grouped by expert."""
+    lib = _load()
+    props = np.ascontiguousarray(props, dtype=np.float32).reshape(-1, 4)
+    n = props.shape[0]
+    if scene is not None:
+        scene = np.ascontiguousarray(scene, dtype=np.int32)
+        assert scene.shape == (n,)
+    expert = np.empty((max(n_scenes, 1),), np.int32)
+    counts = np.empty((3,), np.int32)
+    order = np.empty((max(n_scenes, 1),), np.int32)
+    _chk(lib.emc2o_dispatch(_p(props), _p(scene), n, int(n_scenes), float(np.float32(dist)), float(np.float32(conf)),
+                            _p(expert), _p(counts), _p(order)), "dispatch")
+    return expert[:n_scenes].copy(), counts, order[:n_scenes].copy()
 
 
 def spconv(x: np.ndarray, w: np.ndarray, scale: Optional[np.ndarray], shift: Optional[np.ndarray],

@@ -21,7 +21,9 @@
  *     grouped by the cell of a grid of configurable cell size, and their features pooled per cell
  *     (mean or max);
  *   - multimodal fusion (Sec. 3.1, Fig. 5 caption): the union of LiDAR voxels and pooled image cells,
- *     features concatenated, the missing half zero-filled.
+ *     features concatenated, the missing half zero-filled;
+ *   - Scenario-Adaptive Dispatcher (Sec. 3.2): one of three experts per scene from the distances and
+ *     confidences of its proposal regions, and the scenes grouped by expert.
  *
  * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
  * defined by IEEE fp32 subtract, divide, floor).
@@ -459,6 +461,47 @@ int64_t emc2o_fuse(const int32_t* coords_l, const float* feats_l, int64_t n_l, i
   free(kl);
   free(ki);
   return n;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Scenario-Adaptive Dispatcher                                                                */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * Expert of every scene (Sec. 3.2).  props[i] = (x, y, z, confidence) of proposal region i, scene[i] its
+ * scene.  A proposal is "far" unless fl(fl(x*x) + fl(y*y)) < fl(D*D) (range in the ground plane, compared
+ * squared in fp32), "unclear" unless confidence >= C; a NaN therefore counts as far / unclear.
+ *   expert 2 (accuracy-prioritised):  some proposal is far and unclear;
+ *   expert 1 (versatile efficiency):  otherwise, some proposal is near and unclear, or far and clear;
+ *   expert 0 (latency-prioritised):   otherwise (every proposal near and clear; also a scene without any).
+ * counts[e] = scenes of expert e; order = the scene indices grouped by expert (0, then 1, then 2), ascending
+ * within a group: the batches each expert's stack runs on.  Proposals with a scene id outside
+ * [0, n_scenes) are ignored.  Returns 0 or a negative error.
+ */
+int32_t emc2o_dispatch(const float* props, const int32_t* scene, int64_t n, int32_t n_scenes, float dist,
+                       float conf, int32_t* expert, int32_t* counts, int32_t* order) {
+  if (n < 0 || n_scenes < 0 || !(dist >= 0.0f)) return EMC2O_ERR_ARG;
+  volatile float d2v = dist * dist;
+  const float d2 = d2v;
+  for (int32_t s = 0; s < n_scenes; ++s) expert[s] = 0;
+  for (int64_t i = 0; i < n; ++i) {
+    const int32_t s = scene ? scene[i] : 0;
+    if (s < 0 || s >= n_scenes) continue;
+    const float* p = props + 4 * i;
+    volatile float xx = p[0] * p[0];
+    volatile float yy = p[1] * p[1];
+    volatile float r2v = xx + yy;
+    const float r2 = r2v;
+    const int far = !(r2 < d2);
+    const int unclear = !(p[3] >= conf);
+    const int e = (far && unclear) ? 2 : ((far || unclear) ? 1 : 0);
+    if (e > expert[s]) expert[s] = e;
+  }
+  counts[0] = counts[1] = counts[2] = 0;
+  for (int32_t s = 0; s < n_scenes; ++s) counts[expert[s]]++;
+  int32_t at[3] = {0, counts[0], counts[0] + counts[1]};
+  for (int32_t s = 0; s < n_scenes; ++s) order[at[expert[s]]++] = s;
+  return 0;
 }
 
 /* ------------------------------------------------------------------------------------------- */

@@ -272,3 +272,41 @@ def make_depth(height: int, width: int, seed: int, proposals_only: bool = False,
     if proposals_only:
         depth = np.where(mask, depth, 0.0)
     return np.ascontiguousarray(depth.astype(np.float32))
+
+
+def make_proposals(n_scenes: int, seed: int, dist: float = 23.5, conf: float = 0.5,
+                   max_per_scene: int = 300) -> Tuple[np.ndarray, np.ndarray]:
+    """Proposal regions of `n_scenes` driving scenes: props[N][4] float32 (x, y, z, confidence) and scene[N] int32,
+    shuffled.  A third of the scenes hold only near, confidently detected objects, a third add a few that are
+    near but unclear or far but clear, a third also some that are far and unclear (confidence falls with range,
+    as sparse returns make distant objects hard); a few scenes are empty."""
+    st = Stream(seed, 5000)
+    kinds = (st.bits(n_scenes) % np.uint64(3)).astype(np.int64)
+    sizes = (st.bits(n_scenes) % np.uint64(max_per_scene + 1)).astype(np.int64)
+    sizes[(st.bits(n_scenes) % np.uint64(16)) == 0] = 0
+    props, scenes = [], []
+    for s in range(n_scenes):
+        k = int(sizes[s])
+        if k == 0:
+            continue
+        r = st.uniform(k, 2.0, 0.97 * dist)
+        a = st.uniform(k, -math.pi / 2, math.pi / 2)
+        c = st.uniform(k, min(1.0, conf + 0.05), 1.0)
+        odd = st.uniform(k, 0.0, 1.0) < 0.05                      # the few objects that change the scene's class
+        far = st.uniform(k, 0.0, 1.0) < 0.5
+        if kinds[s] >= 1:
+            r = np.where(odd & far, st.uniform(k, 1.02 * dist, 3.0 * dist), r)           # far but clear
+            c = np.where(odd & ~far, st.uniform(k, 0.0, max(conf - 0.05, 0.0)), c)       # near but unclear
+        if kinds[s] == 2:
+            both = st.uniform(k, 0.0, 1.0) < 0.03
+            r = np.where(both, st.uniform(k, 1.02 * dist, 3.0 * dist), r)
+            c = np.where(both, st.uniform(k, 0.0, max(conf - 0.05, 0.0)), c)
+        z = st.uniform(k, -1.6, 0.4)
+        props.append(np.stack([r * np.cos(a), r * np.sin(a), z, c], axis=1))
+        scenes.append(np.full(k, s, np.int64))
+    if not props:
+        return np.zeros((0, 4), np.float32), np.zeros((0,), np.int32)
+    p = np.concatenate(props).astype(np.float32)
+    sc = np.concatenate(scenes).astype(np.int32)
+    perm = st.permutation(len(p))
+    return np.ascontiguousarray(p[perm]), np.ascontiguousarray(sc[perm])
