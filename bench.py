@@ -477,6 +477,33 @@ def main() -> int:
     except Exception as exc:
         bridge = {"error": repr(exc)}
 
+    # Scenario-Adaptive Dispatcher (outside the timed region): one batch of 8 scenes as in config 5, and a large
+    # batch of 1024 scenes; 20 B per proposal read, 8 B per scene written.
+    disp = None
+    try:
+        disp = []
+        for n_sc in (8, 1024):
+            pr_np, sc_np = gen.make_proposals(n_sc, seed)
+            pr, sc_t = torch.from_numpy(pr_np).cuda(), torch.from_numpy(sc_np).cuda()
+            ex = torch.empty((n_sc,), dtype=torch.int32, device="cuda")
+            cn = torch.empty((3,), dtype=torch.int32, device="cuda")
+            od = torch.empty((n_sc,), dtype=torch.int32, device="cuda")
+            for _ in range(3):
+                ctx.dispatch(pr, sc_t, n_sc, 23.5, 0.5, ex, cn, od)
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0_.record()
+            for _ in range(20):
+                ctx.dispatch(pr, sc_t, n_sc, 23.5, 0.5, ex, cn, od)
+            e1_.record()
+            torch.cuda.synchronize()
+            ms_d = e0_.elapsed_time(e1_) / 20.0
+            db = len(pr_np) * 20.0 + n_sc * 8.0
+            disp.append({"scenes": n_sc, "proposals": len(pr_np), "ms": ms_d, "scenes_per_expert": cn.tolist(),
+                         "algorithmic_MB": db / 1e6, "GB/s": db / (ms_d * 1e-3) / 1e9})
+    except Exception as exc:
+        disp = {"error": repr(exc)}
+
     # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
     # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
     vox_scaling = []
@@ -535,6 +562,7 @@ def main() -> int:
         "project_gather": pg,
         "decoder_side": dec,
         "multimodal_bridge": bridge,
+        "dispatcher": disp,
         "voxelize_scaling": vox_scaling,
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
                          "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),

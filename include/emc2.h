@@ -263,6 +263,26 @@ emc2_status emc2_fuse(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_coords_l
                       int32_t* d_coords_out, void* d_feats_out, int32_t* d_src_l, int32_t* d_src_i, int32_t* d_n_out,
                       int32_t* h_n_out, void* stream);
 
+typedef enum { EMC2_EXPERT_LPE = 0, EMC2_EXPERT_VEE = 1, EMC2_EXPERT_APE = 2 } emc2_expert;
+
+/*
+ * Scenario-Adaptive Dispatcher (paper Sec. 3.2): the expert of every scene of a batch, from the distance and the
+ * confidence of its proposal regions, and the scenes grouped by expert.
+ *   d_props [n_props][4] fp32 (x, y, z, confidence) of each proposal region; d_scene [n_props] int32 its scene,
+ *   or NULL (all in scene 0); ids outside [0, n_scenes) are ignored.
+ *   A proposal is "far" unless fl(fl(x*x) + fl(y*y)) < fl(dist*dist) (range in the ground plane, fp32), "unclear"
+ *   unless confidence >= conf; a NaN therefore counts as far / unclear.
+ *     EMC2_EXPERT_APE (accuracy-prioritised): some proposal of the scene is far and unclear;
+ *     EMC2_EXPERT_VEE (versatile efficiency): otherwise, some proposal is near and unclear, or far and clear;
+ *     EMC2_EXPERT_LPE (latency-prioritised):  otherwise (all near and clear; also a scene without proposals).
+ *   d_expert [n_scenes] int32; d_counts [3] int32 scenes per expert; d_order [n_scenes] int32: scene indices grouped
+ *   by expert (LPE, VEE, APE), ascending within a group: expert e runs on d_order[sum(counts[:e]) ...][counts[e]].
+ *   dist >= 0 (the paper uses 23.5 m and 35 m); 1 <= n_scenes <= 2^20.  Integer results, exact.
+ */
+emc2_status emc2_dispatch(emc2_ctx* ctx, const float* d_props, const int32_t* d_scene, int64_t n_props,
+                          int32_t n_scenes, float dist, float conf, int32_t* d_expert, int32_t* d_counts,
+                          int32_t* d_order, void* stream);
+
 /*
  * Point -> image projection with bilinear feature gather (paper Sec. 3.1: image features are
  * aligned with 3D positions for fusion; Fig. 5 caption: sites without a match get zero-filled

@@ -29,7 +29,7 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
-           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse"]
+           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch"]
 
 
 class Emc2Error(RuntimeError):
@@ -84,6 +84,8 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_fuse.restype = ctypes.c_int
     lib.emc2_fuse.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp, vp, i64, i32, ctypes.POINTER(i32), i32, i32,
                               i64, i32, vp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
+    lib.emc2_dispatch.restype = ctypes.c_int
+    lib.emc2_dispatch.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
     lib.emc2_project_gather.restype = ctypes.c_int
     lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
     lib.emc2_build_inverse_kmap.restype = ctypes.c_int
@@ -277,6 +279,24 @@ class Context:
                                      _ptr(coords_out), _ptr(feats_out), _ptr(src_l), _ptr(src_i), _ptr(n_out),
                                      ctypes.byref(h_n) if sync_count else None, _stream()))
         return int(h_n.value) if sync_count else None
+
+    def dispatch(self, props: torch.Tensor, scene: Optional[torch.Tensor], n_scenes: int, dist: float, conf: float,
+                 expert: torch.Tensor, counts: torch.Tensor, order: torch.Tensor) -> None:
+        """props[N][4] f32 (x, y, z, confidence), scene[N] i32 -> expert[S], counts[3], order[S] (scenes grouped by expert)."""
+        _dev_check(props, torch.float32, "props")
+        for t, nm in ((expert, "expert"), (counts, "counts"), (order, "order")):
+            _dev_check(t, torch.int32, nm)
+        n = int(props.shape[0]) if props.dim() == 2 else 0
+        if props.dim() != 2 or props.shape[1] != 4:
+            raise ValueError("props must be [N][4]")
+        if scene is not None:
+            _dev_check(scene, torch.int32, "scene")
+            if scene.numel() != n:
+                raise ValueError("scene length != number of proposals")
+        if expert.numel() < n_scenes or order.numel() < n_scenes or counts.numel() < 3:
+            raise ValueError("output buffers too small")
+        self._chk(self.lib.emc2_dispatch(self.h, _ptr(props), _ptr(scene), n, n_scenes, dist, conf, _ptr(expert),
+                                         _ptr(counts), _ptr(order), _stream()))
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))
