@@ -121,6 +121,9 @@ def main() -> int:
                     help="issue every launch from the host (default: each context's frame is recorded once into a HIP "
                          "graph and replayed; the steps that carry the dominant kernel's event brackets stay eager)")
     ap.add_argument("--no-scaling-sweep", action="store_true", help="skip the voxelizer batch-size sweep")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip every side measurement outside the timed region (projection, decoder side, pooling and "
+                         "fusion, dispatcher, voxelizer sweep): for counter runs, where every kernel is serialised")
     ap.add_argument("--copy-probe-mib", type=int, default=0,
                     help="also launch one plain device copy of this many MiB (a known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -331,6 +334,8 @@ def main() -> int:
     # 375 x 1242 x 64 fp16 feature map): 16 B + 4 corners x 128 B + 128 B + 1 B per point
     pg = None
     try:
+        if args.headline_only:
+            raise RuntimeError("skipped (--headline-only)")
         cfg3 = get_config(3)
         cam = cfg3.camera
         pts3_np, _ = gen.make_frames(cfg3)
@@ -362,6 +367,8 @@ def main() -> int:
     # layer, the transposed 64->64 conv over it, and the bird's-eye-view flattening of the coarsest level.
     dec = None
     try:
+        if args.headline_only:
+            raise RuntimeError("skipped (--headline-only)")
         runner.run(pts, batch)
         torch.cuda.synchronize()
         fine, coarse = runner.levels[-2], runner.levels[-1]
@@ -417,6 +424,8 @@ def main() -> int:
     # fused site.
     bridge = None
     try:
+        if args.headline_only:
+            raise RuntimeError("skipped (--headline-only)")
         cfg3 = get_config(3)
         cam = cfg3.camera
         npix = cam.height * cam.width
@@ -481,6 +490,8 @@ def main() -> int:
     # batch of 1024 scenes; 20 B per proposal read, 8 B per scene written.
     disp = None
     try:
+        if args.headline_only:
+            raise RuntimeError("skipped (--headline-only)")
         disp = []
         for n_sc in (8, 1024):
             pr_np, sc_np = gen.make_proposals(n_sc, seed)
@@ -507,7 +518,7 @@ def main() -> int:
     # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
     # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
     vox_scaling = []
-    if args.config == 2 and not args.no_scaling_sweep:
+    if args.config == 2 and not args.no_scaling_sweep and not args.headline_only:
         try:
             from paper_2507_04123_amd.configs import VoxelSpec
             for nb_ in (1, 8, 32):
