@@ -56,6 +56,10 @@ def _load():
                                      vp, vp]
     lib.emc2o_fuse.restype = c_i64
     lib.emc2o_fuse.argtypes = [vp, vp, c_i64, c_i32, vp, vp, c_i64, c_i32, vp, c_i32, c_i64, vp, vp, vp, vp]
+    lib.emc2o_quantize_i8.restype = c_i32
+    lib.emc2o_quantize_i8.argtypes = [vp, c_i64, c_f, vp]
+    lib.emc2o_spconv_i8.restype = c_i64
+    lib.emc2o_spconv_i8.argtypes = [vp, c_i64, vp, vp, vp, c_i32, c_f, vp, c_i64, c_i64, c_i32, c_i32, vp, vp]
     lib.emc2o_dispatch.restype = c_i32
     lib.emc2o_dispatch.argtypes = [vp, vp, c_i64, c_i32, c_f, c_f, vp, vp, vp]
     lib.emc2o_project_gather.restype = c_i32
@@ -198,6 +202,37 @@ def fuse(coords_l: np.ndarray, feats_l: np.ndarray, coords_i: np.ndarray, feats_
                             int(n_batch), cap, _p(coords), _p(feats), _p(src_l), _p(src_i)), "fuse")
     res = (coords[:n].copy(), feats[:n].copy())
     return res + (src_l[:n].copy(), src_i[:n].copy()) if want_src else res
+
+
+def quantize_i8(x: np.ndarray, inv_scale: float) -> np.ndarray:
+    """q = clamp(rint(fl32(x * inv_scale)), -127, 127), ties to even."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.shape, np.int8)
+    _chk(lib.emc2o_quantize_i8(_p(x), x.size, float(np.float32(inv_scale)), _p(q)), "quantize_i8")
+    return q
+
+
+def spconv_i8(xq: np.ndarray, wq: np.ndarray, mul: np.ndarray, add: np.ndarray, relu: bool, nbr: np.ndarray,
+              inv_out_scale: Optional[float] = None):
+    """int8 x[n][Cin], int8 w[27][Cin][Cout], fp32 mul/add[Cout], nbr[27][V] -> v[V][Cout] f32 (and int8 q if
+    inv_out_scale is given): exact integer accumulation, v = fl(fl(acc * mul) + add), optional ReLU, re-quantisation."""
+    lib = _load()
+    xq = np.ascontiguousarray(xq, dtype=np.int8)
+    wq = np.ascontiguousarray(wq, dtype=np.int8)
+    mul = np.ascontiguousarray(mul, dtype=np.float32)
+    add = np.ascontiguousarray(add, dtype=np.float32)
+    nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+    n_in, cin = xq.shape
+    assert wq.shape[0] == 27 and wq.shape[1] == cin and nbr.shape[0] == 27
+    cout = wq.shape[2]
+    n_out = nbr.shape[1]
+    v = np.empty((n_out, cout), np.float32)
+    q = np.empty((n_out, cout), np.int8) if inv_out_scale is not None else None
+    _chk(lib.emc2o_spconv_i8(_p(xq), n_in, _p(wq), _p(mul), _p(add), int(bool(relu)),
+                             float(np.float32(inv_out_scale if inv_out_scale is not None else 0.0)), _p(nbr),
+                             max(n_out, 0), n_out, cin, cout, _p(v), _p(q)), "spconv_i8")
+    return (v, q) if inv_out_scale is not None else v
 
 
 LPE, VEE, APE = 0, 1, 2

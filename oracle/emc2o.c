@@ -23,7 +23,10 @@
  *   - multimodal fusion (Sec. 3.1, Fig. 5 caption): the union of LiDAR voxels and pooled image cells,
  *     features concatenated, the missing half zero-filled;
  *   - Scenario-Adaptive Dispatcher (Sec. 3.2): one of three experts per scene from the distances and
- *     confidences of its proposal regions, and the scenes grouped by expert.
+ *     confidences of its proposal regions, and the scenes grouped by expert;
+ *   - quantised sparse convolution (Sec. 3.6 (2) names model quantisation without giving a scheme; the
+ *     scheme here is this build's own): int8 features and weights, exact integer accumulation, a
+ *     per-channel fp32 multiply-add, optional ReLU, optional re-quantisation to int8.
  *
  * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
  * defined by IEEE fp32 subtract, divide, floor).
@@ -560,6 +563,69 @@ int64_t emc2o_spconv(const float* x, int64_t n_in, const float* w, const float* 
 /* ------------------------------------------------------------------------------------------- */
 /* projection + bilinear gather                                                                */
 /* ------------------------------------------------------------------------------------------- */
+
+/* ------------------------------------------------------------------------------------------- */
+/* quantised sparse convolution                                                                */
+/* ------------------------------------------------------------------------------------------- */
+
+/* q = clamp(rint(fl(x * inv_scale)), -127, 127), ties to even; NaN -> 0. */
+static int8_t quant_i8(float x, float inv_scale) {
+  volatile float t = x * inv_scale;
+  float r = rintf(t); /* default rounding mode: to nearest, ties to even */
+  if (!(r == r)) return 0;
+  if (r > 127.0f) r = 127.0f;
+  if (r < -127.0f) r = -127.0f;
+  return (int8_t)r;
+}
+
+int32_t emc2o_quantize_i8(const float* x, int64_t n, float inv_scale, int8_t* q) {
+  if (n < 0) return EMC2O_ERR_ARG;
+  for (int64_t i = 0; i < n; ++i) q[i] = quant_i8(x[i], inv_scale);
+  return 0;
+}
+
+/*
+ * acc[o][c'] = sum over taps k with nbr[k][o] >= 0, sum over c: xq[nbr[k][o]][c] * wq[k][c][c'], exact integers;
+ * v = fl(fl((float)acc * mul[c']) + add[c'])   (int -> fp32 to nearest; product and sum rounded separately, no
+ * fused multiply-add); relu: v = max(v, 0).  out_v receives v.  If out_q is given it receives
+ * quant_i8(v, inv_out_scale).  Returns the number of multiply-accumulates, or a negative error.
+ */
+int64_t emc2o_spconv_i8(const int8_t* xq, int64_t n_in, const int8_t* wq, const float* mul, const float* add,
+                        int32_t relu, float inv_out_scale, const int32_t* nbr, int64_t nbr_stride, int64_t n_out,
+                        int32_t cin, int32_t cout, float* out_v, int8_t* out_q) {
+  if (n_out < 0 || n_out > nbr_stride || cin < 1 || cout < 1 || !mul || !add) return EMC2O_ERR_ARG;
+  int64_t* acc = (int64_t*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)cout, sizeof(int64_t));
+  if (!acc) return EMC2O_ERR_NOMEM;
+  int64_t macs = 0;
+  for (int k = 0; k < 27; ++k) {
+    const int8_t* wk = wq + (int64_t)k * cin * cout;
+    for (int64_t o = 0; o < n_out; ++o) {
+      const int32_t j = nbr[(int64_t)k * nbr_stride + o];
+      if (j < 0) continue;
+      if (j >= n_in) { free(acc); return EMC2O_ERR_ARG; }
+      const int8_t* xr = xq + (int64_t)j * cin;
+      int64_t* ar = acc + o * cout;
+      for (int c = 0; c < cin; ++c) {
+        const int64_t xv = xr[c];
+        const int8_t* wr = wk + (int64_t)c * cout;
+        for (int cc = 0; cc < cout; ++cc) ar[cc] += xv * (int64_t)wr[cc];
+      }
+      macs += (int64_t)cin * cout;
+    }
+  }
+  for (int64_t o = 0; o < n_out; ++o)
+    for (int cc = 0; cc < cout; ++cc) {
+      const float a = (float)acc[o * cout + cc];
+      volatile float p = a * mul[cc];
+      volatile float sum = p + add[cc];
+      float v = sum;
+      if (relu && !(v > 0.0f)) v = 0.0f;
+      out_v[o * cout + cc] = v;
+      if (out_q) out_q[o * cout + cc] = quant_i8(v, inv_out_scale);
+    }
+  free(acc);
+  return macs;
+}
 
 /*
  * (U, V, w) = P (x, y, z, 1); u = U/w, v = V/w; valid iff w > 0, 0 <= u <= W-1, 0 <= v <= H-1.
