@@ -75,7 +75,7 @@ typedef struct {
   int32_t stride_f; /* floats per point row (>= 4): x, y, z, intensity, ...            */
 } emc2_voxel_spec;
 
-typedef enum { EMC2_F32 = 0, EMC2_F16 = 1, EMC2_BF16 = 2 } emc2_dtype;
+typedef enum { EMC2_F32 = 0, EMC2_F16 = 1, EMC2_BF16 = 2, EMC2_I8 = 3 } emc2_dtype;  /* I8: quantised conv only */
 
 /*
  * Voxelization with mean voxel features (paper Sec. 2: LiDAR methods process point clouds via
@@ -262,6 +262,29 @@ emc2_status emc2_fuse(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_coords_l
                       const int32_t grid[3], int32_t n_batch, int32_t out_slot, int64_t capacity_out, int32_t c_out,
                       int32_t* d_coords_out, void* d_feats_out, int32_t* d_src_l, int32_t* d_src_i, int32_t* d_n_out,
                       int32_t* h_n_out, void* stream);
+
+/*
+ * Quantised sparse convolution (paper Sec. 3.6 (2): model quantisation is one of the deployment optimisations; the
+ * paper gives no scheme, this one is the library's own):
+ *   acc[o][c'] = sum_{k : nbr[k][o] >= 0} sum_c xq[nbr[k][o]][c] * wq[k][c][c']        int8 x int8 -> int32, exact
+ *   v          = fl(fl((float)acc * mul[c']) + add[c'])                                 fp32, no fused multiply-add
+ *   v          = max(v, 0) if relu
+ *   out        = F16: v rounded to nearest even;  I8: clamp(rint(fl(v * inv_out_scale)), -127, 127), ties to even
+ * mul[c'] carries input scale x weight scale x folded-BN scale, add[c'] the folded-BN shift: the caller folds them.
+ *   d_in [n_in][Cin] int8; d_w_packed from emc2_pack_weights_i8 (d_w [27][Cin][Cout] int8 -> same byte size);
+ *   d_mul, d_add [Cout] fp32; d_nbr, d_n_out, capacity_out as for emc2_spconv; d_out [capacity_out][Cout] of out_dtype.
+ * Cin in {64, 128}, Cout in {32, 64} (emc2_spconv_i8_supported; others EMC2_ERR_UNSUPPORTED).  Every step is
+ * exact or individually rounded, so the result does not depend on the order of anything.
+ * emc2_quantize_i8: q[i] = clamp(rint(fl((float)x[i] * inv_scale)), -127, 127) (NaN -> 0) for x of F32 or F16.
+ */
+int32_t emc2_spconv_i8_supported(int32_t cin, int32_t cout);
+emc2_status emc2_quantize_i8(emc2_ctx* ctx, emc2_dtype dtype, const void* d_x, int64_t n, float inv_scale, int8_t* d_q,
+                             void* stream);
+emc2_status emc2_pack_weights_i8(emc2_ctx* ctx, const int8_t* d_w, int32_t cin, int32_t cout, void* d_packed, void* stream);
+emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const void* d_w_packed, const float* d_mul,
+                           const float* d_add, int32_t relu, emc2_dtype out_dtype, float inv_out_scale,
+                           const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t cin, int32_t cout,
+                           void* d_out, void* stream);
 
 typedef enum { EMC2_EXPERT_LPE = 0, EMC2_EXPERT_VEE = 1, EMC2_EXPERT_APE = 2 } emc2_expert;
 

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libemc2.so")
 
 OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = 0, 1, 2, 3, 4
-F32, F16, BF16 = 0, 1, 2
+F32, F16, BF16, I8 = 0, 1, 2, 3
 SUBM, STRIDED = 0, 1
 EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
 W_PLAIN, W_PACKED = 0, 1
@@ -29,7 +29,8 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
-           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch"]
+           "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch", "emc2_spconv_i8_supported",
+           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8"]
 
 
 class Emc2Error(RuntimeError):
@@ -84,6 +85,14 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_fuse.restype = ctypes.c_int
     lib.emc2_fuse.argtypes = [vp, ctypes.c_int, vp, vp, vp, i64, i32, vp, vp, vp, i64, i32, ctypes.POINTER(i32), i32, i32,
                               i64, i32, vp, vp, vp, vp, vp, ctypes.POINTER(i32), vp]
+    lib.emc2_spconv_i8_supported.restype = i32
+    lib.emc2_spconv_i8_supported.argtypes = [i32, i32]
+    lib.emc2_quantize_i8.restype = ctypes.c_int
+    lib.emc2_quantize_i8.argtypes = [vp, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp]
+    lib.emc2_pack_weights_i8.restype = ctypes.c_int
+    lib.emc2_pack_weights_i8.argtypes = [vp, vp, i32, i32, vp, vp]
+    lib.emc2_spconv_i8.restype = ctypes.c_int
+    lib.emc2_spconv_i8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, ctypes.c_float, vp, vp, i64, i32, i32, vp, vp]
     lib.emc2_dispatch.restype = ctypes.c_int
     lib.emc2_dispatch.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
     lib.emc2_project_gather.restype = ctypes.c_int
@@ -297,6 +306,46 @@ class Context:
             raise ValueError("output buffers too small")
         self._chk(self.lib.emc2_dispatch(self.h, _ptr(props), _ptr(scene), n, n_scenes, dist, conf, _ptr(expert),
                                          _ptr(counts), _ptr(order), _stream()))
+
+    def spconv_i8_supported(self, cin: int, cout: int) -> bool:
+        return bool(self.lib.emc2_spconv_i8_supported(cin, cout))
+
+    def quantize_i8(self, x: torch.Tensor, inv_scale: float, q: torch.Tensor) -> None:
+        """q = clamp(rint(x * inv_scale), -127, 127) for an F32 or F16 tensor x."""
+        dt = {torch.float32: F32, torch.float16: F16}[x.dtype]
+        _dev_check(x, x.dtype, "x")
+        _dev_check(q, torch.int8, "q")
+        if q.numel() < x.numel():
+            raise ValueError("q smaller than x")
+        self._chk(self.lib.emc2_quantize_i8(self.h, dt, _ptr(x), x.numel(), inv_scale, _ptr(q), _stream()))
+
+    def pack_weights_i8(self, w: torch.Tensor, packed: torch.Tensor) -> None:
+        """w [27][Cin][Cout] int8 -> packed (same size) in the int8 matrix-core fragment order."""
+        _dev_check(w, torch.int8, "w")
+        _dev_check(packed, torch.int8, "packed")
+        if w.dim() != 3 or w.shape[0] != 27 or packed.numel() != w.numel():
+            raise ValueError("w must be [27][Cin][Cout] and packed the same size")
+        self._chk(self.lib.emc2_pack_weights_i8(self.h, _ptr(w), int(w.shape[1]), int(w.shape[2]), _ptr(packed), _stream()))
+
+    def spconv_i8(self, x: torch.Tensor, w_packed: torch.Tensor, cin: int, cout: int, mul: torch.Tensor, add: torch.Tensor,
+                  relu: bool, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int, out: torch.Tensor,
+                  inv_out_scale: float = 0.0) -> None:
+        """Quantised conv: x [n][Cin] int8, packed int8 weights, out [cap][Cout] int8 (re-quantised) or float16."""
+        _dev_check(x, torch.int8, "x")
+        _dev_check(w_packed, torch.int8, "w_packed")
+        _dev_check(mul, torch.float32, "mul")
+        _dev_check(add, torch.float32, "add")
+        _dev_check(nbr, torch.int32, "nbr")
+        _dev_check(n_out, torch.int32, "n_out")
+        if out.dtype not in (torch.int8, torch.float16) or not out.is_cuda or not out.is_contiguous():
+            raise ValueError("out must be a contiguous int8 or float16 device tensor")
+        if x.dim() != 2 or x.shape[1] != cin or w_packed.numel() != 27 * cin * cout or mul.numel() != cout or add.numel() != cout:
+            raise ValueError("shape mismatch")
+        if out.numel() < capacity_out * cout or nbr.numel() < 27 * capacity_out:
+            raise ValueError("out / nbr smaller than capacity_out")
+        self._chk(self.lib.emc2_spconv_i8(self.h, _ptr(x), _ptr(w_packed), _ptr(mul), _ptr(add), int(bool(relu)),
+                                          I8 if out.dtype == torch.int8 else F16, inv_out_scale, _ptr(nbr), _ptr(n_out),
+                                          capacity_out, cin, cout, _ptr(out), _stream()))
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libemc2.so")
-SOURCES = ["context.hip", "cellindex.hip", "voxelize.hip", "kmap.hip", "spconv.hip", "spconv_mfma.hip", "spconv_span.hip", "spconv_direct.hip", "project.hip", "decoder.hip", "pool.hip", "dispatch.hip"]
+SOURCES = ["context.hip", "cellindex.hip", "voxelize.hip", "kmap.hip", "spconv.hip", "spconv_mfma.hip", "spconv_span.hip", "spconv_direct.hip", "project.hip", "decoder.hip", "pool.hip", "dispatch.hip", "spconv_i8.hip"]
 
 
 def build(verbose: bool = False) -> str:
