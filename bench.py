@@ -515,6 +515,48 @@ def main() -> int:
     except Exception as exc:
         disp = {"error": repr(exc)}
 
+    # Quantised conv (outside the timed region): the int8 kernel on the two 64 -> 64 maps of this frame (level-2
+    # submanifold, the shape of the dominant kernel, and the stride-2 map into level 3), beside the fp16 kernel
+    # on the same maps.  Useful operations = 2 x pairs x 64 x 64 against the published dense int8 peak.
+    quant = None
+    try:
+        if args.headline_only:
+            raise RuntimeError("skipped (--headline-only)")
+        runner.run(pts, batch)
+        torch.cuda.synchronize()
+        quant = []
+        for li, layer in enumerate(br.layers):
+            if not (layer.cin == 64 and layer.cout == 64) or any(q_["strided"] == (layer.kind == STRIDED) for q_ in quant):
+                continue
+            lvl_out = sum(1 for l_ in br.layers[:li + 1] if l_.kind == STRIDED)
+            lv_o = runner.levels[lvl_out]
+            nbr_t = lv_o.down_nbr if layer.kind == STRIDED else lv_o.subm_nbr
+            n_in = int(runner.levels[lvl_out - 1].n.item()) if layer.kind == STRIDED else int(lv_o.n.item())
+            xq = torch.randint(-127, 128, (max(n_in, 1), 64), dtype=torch.int8, device="cuda")
+            wq = torch.randint(-60, 61, (27, 64, 64), dtype=torch.int8, device="cuda")
+            wpk = torch.empty((27 * 64 * 64,), dtype=torch.int8, device="cuda")
+            ctx.pack_weights_i8(wq, wpk)
+            ml = torch.full((64,), 1e-5, dtype=torch.float32, device="cuda")
+            ad = torch.zeros((64,), dtype=torch.float32, device="cuda")
+            yq = torch.empty((lv_o.cap, 64), dtype=torch.int8, device="cuda")
+            for _ in range(3):
+                ctx.spconv_i8(xq, wpk, 64, 64, ml, ad, True, nbr_t, lv_o.n, lv_o.cap, yq, inv_out_scale=30.0)
+            e0_, e1_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0_.record()
+            for _ in range(20):
+                ctx.spconv_i8(xq, wpk, 64, 64, ml, ad, True, nbr_t, lv_o.n, lv_o.cap, yq, inv_out_scale=30.0)
+            e1_.record()
+            torch.cuda.synchronize()
+            ms_q = e0_.elapsed_time(e1_) / 20.0
+            ops = 2.0 * layer_pairs[li] * 64 * 64
+            quant.append({"cin": 64, "cout": 64, "strided": layer.kind == STRIDED, "pairs": layer_pairs[li], "ms_int8": ms_q,
+                          "ms_fp16_same_map": conv_ms[li], "useful_TOPS": ops / (ms_q * 1e-3) / 1e12,
+                          "frac_of_int8_peak": ops / (ms_q * 1e-3) / 1e12 / 5000.0})
+            del xq, yq
+    except Exception as exc:
+        quant = {"error": repr(exc)}
+
     # Voxelizer alone at growing batch (the bandwidth claim: one frame is ~6 MB of algorithmic traffic, far too
     # little to be anything but launch- and latency-bound; many frames per launch show what the kernels sustain)
     vox_scaling = []
@@ -574,6 +616,7 @@ def main() -> int:
         "decoder_side": dec,
         "multimodal_bridge": bridge,
         "dispatcher": disp,
+        "quantised_conv": quant,
         "voxelize_scaling": vox_scaling,
         "conv_layers": [{"cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED, "pairs": p, "ms": m,
                          "kernel": ctx.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),
