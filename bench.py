@@ -130,7 +130,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (frames shard across GPUs with no "
-              "exchange; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "exchange, so several GPUs would each run this same program on their share). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -281,7 +281,7 @@ __global__ void __launch_bounds__(256, 4) k_pool_reduce(const __half* __restrict
   int32_t* head_cell = reinterpret_cast<int32_t*>(lds + 64 * C);
   const int g = threadIdx.x >> 3, l = threadIdx.x & 7;
   const int64_t tg = t0 + (int64_t)g * STEPS;  // the group's first row
-  // round 1: which pixel and which cell each row is
+  // first set of loads: which pixel and which cell each row is
   int32_t pix[STEPS], rk[STEPS];
 #pragma unroll
   for (int i = 0; i < STEPS; ++i) {
@@ -293,7 +293,7 @@ __global__ void __launch_bounds__(256, 4) k_pool_reduce(const __half* __restrict
       pix[i] = perm[t];
     }
   }
-  // round 2: the cells' list bounds (the same for every slab)
+  // second set (depends on the first): the cells' list bounds, the same for every slab
   int32_t ca[STEPS], cb[STEPS];
 #pragma unroll
   for (int i = 0; i < STEPS; ++i) {
