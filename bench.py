@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_F16_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E, published
+DTYPE_NAME = {0: "f32", 1: "f16", 2: "bf16"}   # the arithmetic type of the conv operands (accumulation is fp32)
 
 
 class EventTimer:
@@ -292,7 +293,7 @@ def main() -> int:
         dom_launches += 1
     achieved_tflops = dom_flops_total / (dom_ms_total * 1e-3) / 1e12 if dom_ms_total > 0 else 0.0
     roofline = {
-        "kernel": f"{dom_key[0]}<f16, Cin={dom_key[1]}, Cout={dom_key[2]}>",
+        "kernel": f"{dom_key[0]}<{DTYPE_NAME[cfg.dtype]}, Cin={dom_key[1]}, Cout={dom_key[2]}>",
         "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
         "frac": achieved_tflops / PEAK_MFMA_F16_TFLOPS,
         "flops_per_launch": dom_flops_total / max(dom_launches, 1), "launches_per_step": len(dom_layers),
@@ -600,7 +601,7 @@ def main() -> int:
         "metric": "frames/s through voxelize+spconv backbone",
         "value": frames_per_s, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "host_issue_ms_per_step": (t_issued - t0) * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": DTYPE_NAME[cfg.dtype], "data": "synthetic",
         "streams": 1 if args.serial else 2, "frames_in_flight": depth, "hip_graphs": bool(use_graphs),
         "config": {"workload": f"config {cfg.index} ({cfg.name}): {cfg.n_points} points x {cfg.n_frames} frame(s), "
                                f"grid {br.spec.grid}, {len(br.layers)} sparse convs", "capacities": caps,
