@@ -21,6 +21,7 @@ if ROOT not in sys.path:
 
 PEAK_MFMA_F16_TFLOPS = 2500.0      # MI355X dense fp16/bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E, published
+PEAK_VALU_F32_TFLOPS = 157.3       # MI355X fp32 vector ALU, published (256 CUs x 128 lanes x 2 flop x 2.4 GHz)
 DTYPE_NAME = {0: "f32", 1: "f16", 2: "bf16"}   # the arithmetic type of the conv operands (accumulation is fp32)
 
 
@@ -292,10 +293,14 @@ def main() -> int:
         dom_flops_total += layer_flops[tag[1]]
         dom_launches += 1
     achieved_tflops = dom_flops_total / (dom_ms_total * 1e-3) / 1e12 if dom_ms_total > 0 else 0.0
+    # a conv that runs on the matrix cores is priced against their dense 16-bit peak, one on the vector ALU
+    # (fp32, or channel counts no MFMA kernel covers) against the fp32 vector peak
+    dom_on_mfma = bool(ctx.uses_mfma(cfg.dtype, dom_key[1], dom_key[2]))
+    dom_peak = PEAK_MFMA_F16_TFLOPS if dom_on_mfma else PEAK_VALU_F32_TFLOPS
     roofline = {
         "kernel": f"{dom_key[0]}<{DTYPE_NAME[cfg.dtype]}, Cin={dom_key[1]}, Cout={dom_key[2]}>",
-        "bound": "mfma", "achieved": achieved_tflops, "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-        "frac": achieved_tflops / PEAK_MFMA_F16_TFLOPS,
+        "bound": "mfma" if dom_on_mfma else "alu", "achieved": achieved_tflops, "peak": dom_peak, "unit": "TFLOP/s",
+        "frac": achieved_tflops / dom_peak,
         "flops_per_launch": dom_flops_total / max(dom_launches, 1), "launches_per_step": len(dom_layers),
         "avg_launch_ms": dom_ms_total / max(dom_launches, 1), "launches_timed": dom_launches,
         "traffic": profiled_traffic(dom_key[0], cfg.index),
@@ -306,8 +311,8 @@ def main() -> int:
     excl_ms = sum(conv_ms[li] for li in dom_layers)
     excl_flops = sum(layer_flops[li] for li in dom_layers)
     excl_tflops = excl_flops / (excl_ms * 1e-3) / 1e12 if excl_ms > 0 else 0.0
-    roofline_exclusive = {"kernel": roofline["kernel"], "achieved": excl_tflops, "peak": PEAK_MFMA_F16_TFLOPS,
-                          "unit": "TFLOP/s", "frac": excl_tflops / PEAK_MFMA_F16_TFLOPS,
+    roofline_exclusive = {"kernel": roofline["kernel"], "achieved": excl_tflops, "peak": dom_peak,
+                          "unit": "TFLOP/s", "frac": excl_tflops / dom_peak,
                           "avg_launch_ms": excl_ms / max(len(dom_layers), 1),
                           "note": "calibration pass outside the timed region, kernel alone on the GPU"}
 
