@@ -291,3 +291,93 @@ def test_pool_fuse_conv_chain():
     oy = oracle.spconv(x, wgt, None, None, EPI_NONE, onbr)
     assert_features_close(y[:nf].float().cpu().numpy(), oy, 2e-2, "conv over the fused set")
     ctx.close()
+
+
+def test_bridge_and_dispatcher_replay_in_a_hip_graph():
+    """Pooling, fusion and the dispatcher recorded into one HIP graph (serving loops replay them): every replay,
+    with eager work and synchronisations in between and after the input buffers were refilled, gives the oracle's
+    result for the inputs it saw.  None of the three calls may depend on a host round trip or on a memset node."""
+    vs, grid = (0.4, 0.4, 0.4), (176, 200, 10)
+    spec = VoxelSpec(LO, vs, grid)
+    h, w, c = 60, 200, 64
+    scenes = []
+    for seed in (4, 9):
+        pm, q, depth, img = make_scene(seed, h=h, w=w, c=c)
+        lc, lf = _rand_set(seed, grid, 1, 3000, 32, F16)
+        props, scene = gen.make_proposals(8, seed)
+        scenes.append((q, depth, img, lc, lf, props, scene))
+    q = scenes[0][0]
+    # the second scene is lifted with the first scene's camera: only device buffers change between replays
+    cap = h * w + 4000
+    n_prop_cap = max(len(s[5]) for s in scenes)
+    ctx = B.Context(h * w, cap, 176 * 200 * 10, n_slots=2)
+    d_img = torch.zeros((h, w, c), dtype=torch.float16, device="cuda")
+    d_depth = torch.zeros((h, w), dtype=torch.float32, device="cuda")
+    d_lc = torch.zeros((4000, 4), dtype=torch.int32, device="cuda")
+    d_lf = torch.zeros((4000, 32), dtype=torch.float16, device="cuda")
+    n_l = torch.zeros(1, dtype=torch.int32, device="cuda")
+    d_props = torch.zeros((n_prop_cap, 4), dtype=torch.float32, device="cuda")
+    d_scene = torch.full((n_prop_cap,), -1, dtype=torch.int32, device="cuda")     # -1: ignored by the dispatcher
+    ic = torch.zeros((cap, 4), dtype=torch.int32, device="cuda")
+    if_ = torch.zeros((cap, c), dtype=torch.float16, device="cuda")
+    icnt = torch.zeros((cap,), dtype=torch.int32, device="cuda")
+    n_i = torch.zeros(1, dtype=torch.int32, device="cuda")
+    fc = torch.zeros((cap, 4), dtype=torch.int32, device="cuda")
+    ff = torch.zeros((cap, 96), dtype=torch.float16, device="cuda")
+    n_f = torch.zeros(1, dtype=torch.int32, device="cuda")
+    expert = torch.zeros(8, dtype=torch.int32, device="cuda")
+    counts = torch.zeros(3, dtype=torch.int32, device="cuda")
+    order = torch.zeros(8, dtype=torch.int32, device="cuda")
+
+    def fill(s):
+        _, depth, img, lc, lf, props, scene = s
+        d_img.copy_(dev(img)); d_depth.copy_(dev(depth))
+        d_lc.zero_(); d_lc[:len(lc)] = dev(lc); d_lf.zero_(); d_lf[:len(lc)] = dev(lf, torch.float16)
+        n_l.fill_(len(lc))
+        d_props.zero_(); d_props[:len(props)] = dev(props)
+        d_scene.fill_(-1); d_scene[:len(props)] = dev(scene)
+
+    def calls():
+        ctx.pool_image(d_img, d_depth, q, spec, B.POOL_MAX, cap, ic, if_, icnt, n_i, index_slot=0)
+        ctx.fuse(F16, d_lc, d_lf, n_l, 4000, ic, if_, n_i, cap, grid, 1, cap, fc, ff, n_f, out_slot=1)
+        ctx.dispatch(d_props, d_scene, 8, 23.5, 0.5, expert, counts, order)
+
+    def expected(s):
+        _, depth, img, lc, lf, props, scene = s
+        oic, oif, _ = oracle.pool_image(img, depth, q, LO, vs, grid, oracle.POOL_MAX)
+        ofc, off = oracle.fuse(lc, lf, oic, oif, grid)
+        return ofc, off, oracle.dispatch(props, scene, 8, 23.5, 0.5)
+
+    def check(s, what):
+        torch.cuda.synchronize()
+        ctx.status_sync()
+        ofc, off, (oe, ocn, oo) = expected(s)
+        nf = int(n_f.item())
+        assert nf == len(ofc), what
+        assert np.array_equal(fc[:nf].cpu().numpy(), ofc), what
+        assert np.array_equal(ff[:nf].float().cpu().numpy(), off), what
+        assert np.array_equal(expert.cpu().numpy(), oe) and np.array_equal(counts.cpu().numpy(), ocn), what
+        assert np.array_equal(order.cpu().numpy(), oo), what
+
+    fill(scenes[0])
+    calls()
+    check(scenes[0], "eager")
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        calls()                                   # warm-up on the capture stream
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            calls()
+    torch.cuda.synchronize()
+    for it in range(5):
+        s = scenes[it % 2]
+        print(f"bridge graph replay {it}", flush=True)
+        fill(s)
+        torch.cuda.synchronize()
+        graph.replay()
+        check(s, f"replay {it}")
+        if it == 2:
+            calls()                               # eager work between replays
+            check(s, "eager between replays")
+    ctx.close()
