@@ -14,13 +14,22 @@ from paper_2507_04123_amd import gen
 LPE, VEE, APE = 0, 1, 2
 
 
+def _paper_thresholds():
+    """The two distance thresholds the paper prints (tests/golden/, with its citation)."""
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "dispatcher_distance_thresholds.txt")
+    vals = [float(line.split()[1]) for line in open(path) if line.strip() and not line.startswith("#")]
+    assert vals == [23.5, 35.0]
+    return vals
+
+
 def _one_scene(rows, d, c):
     e, counts, order = oracle.dispatch(np.array(rows, np.float32).reshape(-1, 4), None, 1, d, c)
     assert counts.sum() == 1 and order.tolist() == [0] and counts[e[0]] == 1
     return int(e[0])
 
 
-@pytest.mark.parametrize("d", [23.5, 35.0])
+@pytest.mark.parametrize("d", _paper_thresholds())
 def test_three_categories_as_defined(d):
     c = 0.5
     near, far = (0.5 * d, 0.0, 0.0), (0.0, 1.5 * d, 0.0)
