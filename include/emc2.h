@@ -1,14 +1,16 @@
 /*
  * emc2.h -- C-ABI of the MI355X (gfx950) hot path of the EMC2 LiDAR branch:
  *   multi-scale voxelization  ->  27-offset kernel map  ->  sparse 3D conv (+ fused affine/ReLU)
- *   ->  point-to-image projection with bilinear feature gather.
+ *   ->  point-to-image projection with bilinear feature gather,
+ * and on the same data structures: inverse kernel map + bird's-eye-view flattening (decoder side),
+ * Multiscale Pooling of image features + multimodal fusion, the scene dispatcher, an int8 sparse conv.
  *
  * Conventions
  *   - Pointers named d_* are DEVICE pointers (HBM, on the context's device); h_* and plain
  *     struct/array arguments are HOST pointers.  The caller owns every input and output buffer;
- *     the context owns all scratch (per-voxel point stash, cell-index slots, scan partials, status
- *     word),
- *     allocated once in emc2_create.  No call below allocates or frees device memory.
+ *     the context owns all scratch (per-voxel point stash, cell-index slots, scan partials, per-pixel
+ *     sort arrays of the pooling, status word), allocated once in emc2_create.  No call below
+ *     allocates or frees device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls validate their
  *     arguments synchronously, enqueue kernels on `stream` and return; they never block unless a
  *     host count pointer (h_n_*) is given.  Counts (n_voxels, n_out) are produced in DEVICE memory
@@ -17,11 +19,13 @@
  *   - Errors found on the host are returned at once.  Errors only the device can see (more voxels
  *     than `capacity`) set a device status word; emc2_status_sync returns and
  *     clears it.  After such an error the outputs of that call are truncated but in bounds.
- *   - emc2_voxelize, emc2_build_kmap and emc2_spconv with EMC2_W_PLAIN weights on an MFMA shape share
- *     the context's scratch: issue them on one stream at a time.  emc2_spconv with packed (or non-MFMA)
- *     weights, emc2_pack_weights into caller memory and emc2_project_gather touch no mutable context
- *     state and may run on other streams concurrently, ordered by the caller's events (a conv must
- *     wait for the call that wrote the map and features it reads).
+ *   - emc2_voxelize, emc2_build_kmap, emc2_build_inverse_kmap (reads an index slot), emc2_pool_image,
+ *     emc2_fuse and emc2_spconv with EMC2_W_PLAIN weights on an MFMA shape share the context's scratch
+ *     and index slots: issue them on one stream at a time.  emc2_spconv with packed (or non-MFMA)
+ *     weights, emc2_spconv_i8, emc2_quantize_i8, the weight-packing calls into caller memory,
+ *     emc2_bev_flatten, emc2_dispatch and emc2_project_gather touch no mutable context state and may
+ *     run on other streams concurrently, ordered by the caller's events (a conv must wait for the
+ *     call that wrote the map and features it reads).
  *   - Voxel order everywhere: ascending key ((b*Gz + z)*Gy + y)*Gx + x, i.e. lexicographic
  *     (b, z, y, x).  Coordinates are int32 quadruples (b, z, y, x).
  */
@@ -46,11 +50,12 @@ typedef struct emc2_ctx emc2_ctx;
 
 /*
  * Create a context on `device`.
- *   max_points : largest n_points any emc2_voxelize call will pass.
+ *   max_points : largest n_points any emc2_voxelize call will pass; also the largest H*W of an image
+ *                given to emc2_pool_image.
  *   max_voxels : largest voxel count (capacity) of any level.
  *   max_cells  : largest n_batch*Gx*Gy*Gz of any grid that is voxelized or mapped.
  *   n_slots    : number of cell-index slots kept alive at once (>= 1; see emc2_voxelize).
- * Scratch is about 48 B/point-slot + 8 B per 32 cells per index slot.
+ * Scratch is about 32 B per point + 76 B per voxel + 8 B per 32 cells per index slot.
  */
 emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_points, int64_t max_voxels,
                         int64_t max_cells, int32_t n_slots);
