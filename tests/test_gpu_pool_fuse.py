@@ -63,7 +63,7 @@ def check_pool(ctx, img, depth, q, spec, mode, cap, batch_index=0):
 
 
 @pytest.mark.parametrize("mode", [B.POOL_MEAN, B.POOL_MAX])
-@pytest.mark.parametrize("c", [8, 64, 128, 256])
+@pytest.mark.parametrize("c", [8, 24, 64, 128, 200, 256])
 def test_pool_image_small_scenes(mode, c):
     ctx = B.Context(60 * 200, 60 * 200, 1408 * 1600 * 40, n_slots=1)
     pm, q, depth, img = make_scene(5 + c, c=c)
