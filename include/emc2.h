@@ -17,8 +17,10 @@
  *     so that downstream calls need no host round trip: launches are sized by `capacity`, kernels
  *     bound themselves by the device count.
  *   - Errors found on the host are returned at once.  Errors only the device can see (more voxels
- *     than `capacity`) set a device status word; emc2_status_sync returns and
- *     clears it.  After such an error the outputs of that call are truncated but in bounds.
+ *     than `capacity`; a kernel-map entry at or beyond the input's row count) set a device status word;
+ *     emc2_status_sync returns and clears it.  After such an error the outputs of that call are
+ *     truncated (capacity) or computed without the offending entries (map), and every access stayed
+ *     in bounds.
  *   - emc2_voxelize, emc2_build_kmap, emc2_build_inverse_kmap (reads an index slot), emc2_pool_image,
  *     emc2_fuse and emc2_spconv with EMC2_W_PLAIN weights on an MFMA shape share the context's scratch
  *     and index slots: issue them on one stream at a time.  emc2_spconv with packed (or non-MFMA)
@@ -43,7 +45,8 @@ typedef enum {
   EMC2_ERR_INVALID_ARG = 1, /* null/mis-sized argument, size beyond what the context was made for */
   EMC2_ERR_CAPACITY = 2,    /* more voxels than `capacity`                                         */
   EMC2_ERR_UNSUPPORTED = 3, /* channel count / dtype / key width the kernels do not cover          */
-  EMC2_ERR_DEVICE = 4       /* a HIP runtime call failed; see emc2_last_error                      */
+  EMC2_ERR_DEVICE = 4,      /* a HIP runtime call failed; see emc2_last_error                      */
+  EMC2_ERR_MAP = 5          /* a kernel-map entry named a row outside the input (found on the device) */
 } emc2_status;
 
 typedef struct emc2_ctx emc2_ctx;
@@ -145,7 +148,8 @@ typedef enum { EMC2_W_PLAIN = 0, EMC2_W_PACKED = 1 } emc2_wlayout;
 
 /*
  * 1 if (dtype, Cin, Cout) runs on the MFMA kernels (and therefore accepts EMC2_W_PACKED), else 0.
- * Host-only query, no GPU work.
+ * Host-only query about this library's kernel selection: no GPU work, and no passage of the paper stands
+ * behind it.
  */
 int32_t emc2_spconv_uses_mfma(emc2_dtype dtype, int32_t cin, int32_t cout);
 
@@ -169,6 +173,11 @@ emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, 
  *   context scratch by one extra small kernel per call), EMC2_W_PACKED = output of emc2_pack_weights
  *   d_scale, d_shift [Cout] fp32 (NULL iff EMC2_EPI_NONE)
  *   d_nbr [27][capacity_out] from emc2_build_kmap; d_n_out device int32 count of outputs.
+ *   n_in_rows: rows of d_in the caller vouches for (its voxel count if known on the host, else the capacity
+ *   the buffer was allocated with).  An entry of d_nbr at or beyond it is treated as absent -- nothing is read
+ *   through it -- and EMC2_ERR_MAP is reported through the status word.
+ *   For F16/BF16, d_in, d_w and d_out must be 16-byte aligned (EMC2_ERR_INVALID_ARG otherwise): rows move as
+ *   8- and 16-byte pieces.
  * F16/BF16 run on MFMA for Cin in {16,32,64,128} and Cout in {32,64,128}; other channel counts
  * (Cin <= 1024, Cout <= 256) and F32 run on the vector ALU.  Rows [n_out, capacity_out) of d_out
  * are not written.
@@ -178,15 +187,16 @@ emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, 
  */
 #define EMC2_MAP_ANY (-1)
 /*
- * Name of the device kernel emc2_spconv launches for these arguments ("k_spconv_span", "k_spconv_mfma",
- * "k_spconv_small" or "k_spconv_alu"): lets a profile be matched to a layer.  Host-only query; the
- * string is static.  NULL for a dtype emc2_spconv rejects.
+ * Name of the device kernel emc2_spconv launches for these arguments ("k_spconv_span", "k_spconv_direct",
+ * "k_spconv_mfma", "k_spconv_small" or "k_spconv_alu"): lets a profile be matched to a layer.  Host-only
+ * query about this library's kernel selection (no GPU work, no passage of the paper behind it); the string
+ * is static.  NULL for a dtype emc2_spconv rejects.
  */
 const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t cout, int32_t map_hint);
 emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w, emc2_wlayout w_layout,
                         const float* d_scale, const float* d_shift, emc2_epilogue epilogue,
                         const int32_t* d_nbr, int32_t map_hint, const int32_t* d_n_out, int64_t capacity_out,
-                        int32_t cin, int32_t cout, void* d_out, void* stream);
+                        int64_t n_in_rows, int32_t cin, int32_t cout, void* d_out, void* stream);
 
 /*
  * Inverse (transposed) kernel map of a stride-2 layer, for the decoder half of the LiDAR UNet (paper
@@ -277,8 +287,10 @@ emc2_status emc2_fuse(emc2_ctx* ctx, emc2_dtype dtype, const int32_t* d_coords_l
  *   out        = F16: v rounded to nearest even;  I8: clamp(rint(fl(v * inv_out_scale)), -127, 127), ties to even
  * mul[c'] carries input scale x weight scale x folded-BN scale, add[c'] the folded-BN shift: the caller folds them.
  *   d_in [n_in][Cin] int8; d_w_packed from emc2_pack_weights_i8 (d_w [27][Cin][Cout] int8 -> same byte size);
- *   d_mul, d_add [Cout] fp32; d_nbr, d_n_out, capacity_out as for emc2_spconv; d_out [capacity_out][Cout] of out_dtype.
- * Cin in {64, 128}, Cout in {32, 64} (emc2_spconv_i8_supported; others EMC2_ERR_UNSUPPORTED).  Every step is
+ *   d_mul, d_add [Cout] fp32; d_nbr, d_n_out, capacity_out, n_in_rows as for emc2_spconv (entries at or beyond
+ *   n_in_rows are absent and reported); d_out [capacity_out][Cout] of out_dtype; d_in, d_w_packed, d_out 16-byte aligned.
+ * Cin in {64, 128}, Cout in {32, 64} (emc2_spconv_i8_supported, a host-only query about this library's kernels with
+ * no passage of the paper behind it; others EMC2_ERR_UNSUPPORTED).  Every step is
  * exact or individually rounded, so the result does not depend on the order of anything.
  * emc2_quantize_i8: q[i] = clamp(rint(fl((float)x[i] * inv_scale)), -127, 127) (NaN -> 0) for x of F32 or F16.
  */
@@ -288,8 +300,8 @@ emc2_status emc2_quantize_i8(emc2_ctx* ctx, emc2_dtype dtype, const void* d_x, i
 emc2_status emc2_pack_weights_i8(emc2_ctx* ctx, const int8_t* d_w, int32_t cin, int32_t cout, void* d_packed, void* stream);
 emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const void* d_w_packed, const float* d_mul,
                            const float* d_add, int32_t relu, emc2_dtype out_dtype, float inv_out_scale,
-                           const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t cin, int32_t cout,
-                           void* d_out, void* stream);
+                           const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows, int32_t cin,
+                           int32_t cout, void* d_out, void* stream);
 
 typedef enum { EMC2_EXPERT_LPE = 0, EMC2_EXPERT_VEE = 1, EMC2_EXPERT_APE = 2 } emc2_expert;
 

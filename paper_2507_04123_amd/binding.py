@@ -17,7 +17,7 @@ from .configs import VoxelSpec
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libemc2.so")
 
-OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = 0, 1, 2, 3, 4
+OK, ERR_INVALID_ARG, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE, ERR_MAP = 0, 1, 2, 3, 4, 5
 F32, F16, BF16, I8 = 0, 1, 2, 3
 SUBM, STRIDED = 0, 1
 EPI_NONE, EPI_AFFINE, EPI_AFFINE_RELU = 0, 1, 2
@@ -72,7 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_build_kmap.argtypes = [vp, ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i32, i32, i64, vp, vp, vp,
                                     ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
     lib.emc2_spconv.restype = ctypes.c_int
-    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, i32, vp, i64, i32, i32, vp, vp]
+    lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, i32, vp, i64, i64, i32, i32, vp, vp]
     lib.emc2_pack_weights.restype = ctypes.c_int
     lib.emc2_pack_weights.argtypes = [vp, ctypes.c_int, vp, i32, i32, vp, vp]
     lib.emc2_spconv_kernel.restype = ctypes.c_char_p
@@ -92,7 +92,7 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_pack_weights_i8.restype = ctypes.c_int
     lib.emc2_pack_weights_i8.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.emc2_spconv_i8.restype = ctypes.c_int
-    lib.emc2_spconv_i8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, ctypes.c_float, vp, vp, i64, i32, i32, vp, vp]
+    lib.emc2_spconv_i8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, ctypes.c_float, vp, vp, i64, i64, i32, i32, vp, vp]
     lib.emc2_dispatch.restype = ctypes.c_int
     lib.emc2_dispatch.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
     lib.emc2_project_gather.restype = ctypes.c_int
@@ -329,8 +329,9 @@ class Context:
 
     def spconv_i8(self, x: torch.Tensor, w_packed: torch.Tensor, cin: int, cout: int, mul: torch.Tensor, add: torch.Tensor,
                   relu: bool, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int, out: torch.Tensor,
-                  inv_out_scale: float = 0.0) -> None:
-        """Quantised conv: x [n][Cin] int8, packed int8 weights, out [cap][Cout] int8 (re-quantised) or float16."""
+                  inv_out_scale: float = 0.0, n_in_rows: Optional[int] = None) -> None:
+        """Quantised conv: x [n][Cin] int8, packed int8 weights, out [cap][Cout] int8 (re-quantised) or float16.
+        n_in_rows: rows of x a map entry may name (default: all rows of the tensor)."""
         _dev_check(x, torch.int8, "x")
         _dev_check(w_packed, torch.int8, "w_packed")
         _dev_check(mul, torch.float32, "mul")
@@ -345,7 +346,8 @@ class Context:
             raise ValueError("out / nbr smaller than capacity_out")
         self._chk(self.lib.emc2_spconv_i8(self.h, _ptr(x), _ptr(w_packed), _ptr(mul), _ptr(add), int(bool(relu)),
                                           I8 if out.dtype == torch.int8 else F16, inv_out_scale, _ptr(nbr), _ptr(n_out),
-                                          capacity_out, cin, cout, _ptr(out), _stream()))
+                                          capacity_out, int(x.shape[0]) if n_in_rows is None else n_in_rows, cin, cout,
+                                          _ptr(out), _stream()))
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))
@@ -366,7 +368,8 @@ class Context:
 
     def spconv(self, dtype: int, x: torch.Tensor, w: torch.Tensor, scale: Optional[torch.Tensor],
                shift: Optional[torch.Tensor], epilogue: int, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int,
-               out: torch.Tensor, w_layout: int = W_PLAIN, map_hint: int = MAP_ANY) -> None:
+               out: torch.Tensor, w_layout: int = W_PLAIN, map_hint: int = MAP_ANY, n_in_rows: Optional[int] = None) -> None:
+        """n_in_rows: rows of x a map entry may name (default: all rows of the tensor)."""
         td = _TORCH_DTYPE[dtype]
         _dev_check(x, td, "x")
         _dev_check(w, td, "w")
@@ -384,7 +387,8 @@ class Context:
             if scale.numel() != cout or shift.numel() != cout:
                 raise ValueError("scale/shift must have Cout entries")
         self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), w_layout, _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
-                                       map_hint, _ptr(n_out), capacity_out, cin, cout, _ptr(out), _stream()))
+                                       map_hint, _ptr(n_out), capacity_out,
+                                       int(x.shape[0]) if n_in_rows is None else n_in_rows, cin, cout, _ptr(out), _stream()))
 
     def project_gather(self, points: torch.Tensor, pmat: Sequence[float], img: torch.Tensor, out: torch.Tensor,
                        valid: torch.Tensor, uv: Optional[torch.Tensor] = None) -> None:

@@ -46,6 +46,19 @@ __device__ __forceinline__ int4 decode_key(uint64_t key, int gx, int gy, int gz)
 
 // Device status bits (OR-ed by kernels, read by emc2_status_sync).
 #define EMC2_DEVFLAG_CAPACITY 1
+#define EMC2_DEVFLAG_MAP 2        // a kernel-map entry named a row outside [0, n_in_rows)
+
+// A kernel-map entry as a conv kernel uses it.  Rows past n_out (`dead` = -1, else 0) have no neighbours; an
+// entry at or beyond the `n_in` rows the caller says the input holds is treated as absent (never read) and
+// remembered in the wave-uniform mask `oob`, which emc2_report_oob turns into a status bit at the kernel's end.
+__device__ __forceinline__ int32_t emc2_entry(int32_t j, int32_t dead, int32_t n_in, unsigned long long& oob) {
+  j |= dead;
+  oob |= __ballot(j >= n_in);
+  return j < n_in ? j : -1;
+}
+__device__ __forceinline__ void emc2_report_oob(unsigned long long oob, int32_t* __restrict__ flags) {
+  if (oob != 0ull && (threadIdx.x & 63) == 0) atomicOr(flags, EMC2_DEVFLAG_MAP);
+}
 
 struct SlotMeta {
   int32_t grid[3];
@@ -64,7 +77,7 @@ struct emc2_ctx {
   float4* stash;            // [max_voxels][EMC2_VOX_STASH] points of each voxel, in arrival order
   uint32_t* partials;       // scan partial sums
   int64_t n_partials;
-  int32_t* dev_words;       // [0] status flags, [1] distinct-voxel counter, [2] scratch count
+  int32_t* dev_words;       // [0] status flags, [2] voxel count of an index rebuilt from coordinates (others unused)
   void* wpack;              // scratch for weights re-ordered per call (27*128*128 16-bit values)
   void* zero_row;           // 256 zero bytes: the feature row an absent neighbour reads
   // image pooling: per-pixel cell rank / position within the cell / sorted order, per-cell list starts

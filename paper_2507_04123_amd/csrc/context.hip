@@ -127,7 +127,10 @@ extern "C" emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream) {
   if (st != EMC2_OK) return st;
   const int flags = ctx->pinned[0];
   if (flags & EMC2_DEVFLAG_CAPACITY)
-    return emc2_fail(ctx, EMC2_ERR_CAPACITY, "device reported [more voxels than capacity]");
+    return emc2_fail(ctx, EMC2_ERR_CAPACITY, "device reported [more voxels than capacity]%s",
+                     (flags & EMC2_DEVFLAG_MAP) ? " and [kernel-map entry outside the input rows]" : "");
+  if (flags & EMC2_DEVFLAG_MAP)
+    return emc2_fail(ctx, EMC2_ERR_MAP, "device reported [kernel-map entry outside the input rows]");
   return EMC2_OK;
 }
 

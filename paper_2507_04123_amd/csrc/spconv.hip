@@ -22,8 +22,9 @@ template <typename T>
 __global__ void __launch_bounds__(256) k_spconv_alu(const T* __restrict__ in, const T* __restrict__ w,
                                                     const float* __restrict__ scale, const float* __restrict__ shift,
                                                     int epilogue, const int32_t* __restrict__ nbr,
-                                                    const int32_t* __restrict__ d_n_out, int64_t capacity_out, int cin,
-                                                    int cout, int rows_per_block, T* __restrict__ out) {
+                                                    const int32_t* __restrict__ d_n_out, int64_t capacity_out,
+                                                    int32_t n_in, int32_t* __restrict__ dev_flags, int cin, int cout,
+                                                    int rows_per_block, T* __restrict__ out) {
   int64_t n = *d_n_out;
   if (n > capacity_out) n = capacity_out;
   const int row = threadIdx.x / cout;
@@ -34,6 +35,10 @@ __global__ void __launch_bounds__(256) k_spconv_alu(const T* __restrict__ in, co
   for (int k = 0; k < 27; ++k) {
     const int32_t j = nbr[(int64_t)k * capacity_out + o];
     if (j < 0) continue;
+    if (j >= n_in) {   // names a row the input does not hold: absent, and reported
+      if (d == 0) atomicOr(dev_flags, EMC2_DEVFLAG_MAP);
+      continue;
+    }
     const T* xr = in + (int64_t)j * cin;
     const T* wk = w + (int64_t)k * cin * cout + d;
     for (int c = 0; c < cin; ++c) acc = fmaf(to_f32(xr[c]), to_f32(wk[(int64_t)c * cout]), acc);
@@ -58,7 +63,7 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
                                                       const float* __restrict__ scale, const float* __restrict__ shift,
                                                       int epilogue, const int32_t* __restrict__ nbr,
                                                       const int32_t* __restrict__ d_n_out, int64_t capacity_out,
-                                                      T* __restrict__ out) {
+                                                      int32_t n_in, int32_t* __restrict__ dev_flags, T* __restrict__ out) {
   __shared__ float wl[27 * CIN * COUT];
   for (int i = threadIdx.x; i < 27 * CIN * COUT; i += 256) wl[i] = to_f32(w[i]);
   int64_t n = *d_n_out;
@@ -72,6 +77,7 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
   constexpr int RW = ROW_BYTES / 4;               // 32-bit words per feature row
   constexpr int TB = ROW_BYTES <= 8 ? 27 : 9;     // taps whose rows are in flight together
   int32_t j[27];
+  unsigned long long oob = 0ull;   // lanes that saw an entry outside [0, n_in)
 #pragma unroll
   for (int k = 0; k < 27; ++k) j[k] = nrow[(int64_t)k * capacity_out];
   float acc[COUT];
@@ -83,7 +89,7 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
     uint32_t xr[TB][RW];
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
-      const int32_t jj = j[k0 + t] | dead;
+      const int32_t jj = j[k0 + t] = emc2_entry(j[k0 + t], dead, n_in, oob);   // masked once, used twice
       const char* src = reinterpret_cast<const char*>(in + (int64_t)(jj >= 0 ? jj : 0) * CIN);
       if constexpr (ROW_BYTES == 8) {
         const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src);
@@ -99,7 +105,7 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
 #pragma unroll
     for (int t = 0; t < TB; ++t) {
       const int k = k0 + t;
-      const bool have = (j[k] | dead) >= 0;
+      const bool have = j[k] >= 0;
       if (__ballot(have) == 0ull) continue;  // wave-uniform
       if (have) {
         const float* wk = wl + k * CIN * COUT;
@@ -119,6 +125,7 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
       }
     }
   }
+  emc2_report_oob(oob, dev_flags);
   if (!live) return;
   alignas(16) T yr[COUT];
 #pragma unroll
@@ -137,13 +144,13 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
 
 template <typename T>
 bool launch_small(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
-                  const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
-                  hipStream_t s) {
+                  const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+                  int cin, int cout, void* d_out, hipStream_t s) {
 #define EMC2_SMALL(CI, CO)                                                                                            \
   if (cin == CI && cout == CO) {                                                                                      \
     hipLaunchKernelGGL((k_spconv_small<T, CI, CO>), dim3((unsigned)emc2_div_up(capacity_out, 256)), dim3(256), 0, s,  \
                        (const T*)d_in, (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out,       \
-                       (T*)d_out);                                                                                    \
+                       n_in, dev_flags, (T*)d_out);                                                                   \
     return true;                                                                                                      \
   }
   EMC2_SMALL(4, 16) EMC2_SMALL(4, 32) EMC2_SMALL(16, 16)
@@ -153,12 +160,14 @@ bool launch_small(const void* d_in, const void* d_w, const float* d_scale, const
 
 template <typename T>
 void launch_alu(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
-                const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
-                hipStream_t s) {
-  if (launch_small<T>(d_in, d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s)) return;
+                const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+                int cin, int cout, void* d_out, hipStream_t s) {
+  if (launch_small<T>(d_in, d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags, cin, cout, d_out, s))
+    return;
   const int rows = 256 / cout;
   hipLaunchKernelGGL(k_spconv_alu<T>, dim3((unsigned)emc2_div_up(capacity_out, rows)), dim3(256), 0, s, (const T*)d_in,
-                     (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, rows, (T*)d_out);
+                     (const T*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags, cin, cout, rows,
+                     (T*)d_out);
 }
 
 }  // namespace
@@ -197,8 +206,8 @@ extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const 
 extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* d_in, const void* d_w,
                                    emc2_wlayout w_layout, const float* d_scale, const float* d_shift,
                                    emc2_epilogue epilogue, const int32_t* d_nbr, int32_t map_hint,
-                                   const int32_t* d_n_out, int64_t capacity_out, int32_t cin, int32_t cout, void* d_out,
-                                   void* stream) {
+                                   const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows, int32_t cin,
+                                   int32_t cout, void* d_out, void* stream) {
   if (!ctx) return EMC2_ERR_INVALID_ARG;
   if (!d_in || !d_w || !d_nbr || !d_n_out || !d_out)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: null argument");
@@ -207,6 +216,8 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
   if ((epilogue == EMC2_EPI_NONE) != (d_scale == nullptr) || (d_scale == nullptr) != (d_shift == nullptr))
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: scale/shift must be given iff the epilogue is affine");
   if (capacity_out < 1) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: capacity_out < 1");
+  if (n_in_rows < 0) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: n_in_rows < 0");
+  const int32_t n_in = n_in_rows > 0x7fffffff ? 0x7fffffff : (int32_t)n_in_rows;
   if (cin < 1 || cout < 1 || cin > 1024 || cout > 256)
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: channels outside Cin<=1024, Cout<=256");
   if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16)
@@ -218,7 +229,11 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
   const bool mfma = emc2_spconv_uses_mfma(dtype, cin, cout) != 0;
   if (w_layout == EMC2_W_PACKED && !mfma)
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv: packed weights need an MFMA-covered (dtype, Cin, Cout)");
+  // the matrix-core and small-channel kernels move rows as 8- or 16-byte pieces
+  if (dtype != EMC2_F32 && (((uintptr_t)d_in | (uintptr_t)d_out | (uintptr_t)d_w) & 15u))
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv: 16-bit d_in, d_w and d_out must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
+  int32_t* flags = ctx->dev_words;
   if (mfma) {
     const bool direct = emc2_spconv_direct_supported(cin, cout);
     const void* wp = d_w;
@@ -229,21 +244,22 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
       wp = ctx->wpack;
     }
     if (!direct)
-      emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
-                              d_out, s);
+      emc2_spconv_mfma_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags,
+                              cin, cout, d_out, s);
     else if (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout))
       // pays where the three kx taps of a group name nearly the same rows
-      emc2_spconv_span_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
-                              d_out, s);
+      emc2_spconv_span_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags,
+                              cin, cout, d_out, s);
     else
-      emc2_spconv_direct_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout,
-                                ctx->zero_row, d_out, s);
+      emc2_spconv_direct_launch(dtype, d_in, wp, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags,
+                                cin, cout, ctx->zero_row, d_out, s);
   } else if (dtype == EMC2_F32) {
-    launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+    launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags, cin, cout, d_out, s);
   } else if (dtype == EMC2_F16) {
-    launch_alu<__half>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+    launch_alu<__half>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags, cin, cout, d_out, s);
   } else {
-    launch_alu<__hip_bfloat16>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, s);
+    launch_alu<__hip_bfloat16>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags, cin, cout,
+                               d_out, s);
   }
   return emc2_check_hip(ctx, hipGetLastError(), "emc2_spconv launch");
 }

@@ -86,8 +86,8 @@ template <int DT, int CIN, int COUT>
 __global__ void __launch_bounds__(kDThreads, (DirectCfg<CIN, COUT>::MINW))
 k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, const float* __restrict__ scale,
                 const float* __restrict__ shift, int epilogue, const int32_t* __restrict__ nbr,
-                const int32_t* __restrict__ d_n_out, int64_t capacity_out, const uint16_t* __restrict__ zrow,
-                uint16_t* __restrict__ out) {
+                const int32_t* __restrict__ d_n_out, int64_t capacity_out, int32_t n_in, int32_t* __restrict__ dev_flags,
+                const uint16_t* __restrict__ zrow, uint16_t* __restrict__ out) {
   constexpr int KS = CIN / 32;                // k-steps per tap
   constexpr int NT = COUT / 16;               // 16-column tiles
   constexpr int MT = DirectCfg<CIN, COUT>::MT;   // 16-row tiles per wave
@@ -123,6 +123,7 @@ k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, c
   const bool live = wave_row0 + (lane % R) < n_out;
   const int32_t* nrow = nbr + (live ? wave_row0 + (lane % R) : 0);
   const int32_t dead = live ? 0 : -1;   // OR-ed into kernel-map entries: rows past n_out have no neighbours
+  unsigned long long oob = 0ull;        // lanes that saw an entry outside [0, n_in)
 
   floatx4 acc[MT][NT];
 #pragma unroll
@@ -175,9 +176,9 @@ k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, c
   EMC2_W_STORE(0, 0)
   EMC2_W_LOAD(1, 1)
   EMC2_W_LOAD(2, 2)
-  EMC2_A_LOAD(jq[0][0] | dead, 0)
-  EMC2_A_LOAD(jq[0][1] | dead, 1)
-  EMC2_A_LOAD(jq[0][2] | dead, 2)
+  EMC2_A_LOAD(emc2_entry(jq[0][0], dead, n_in, oob), 0)
+  EMC2_A_LOAD(emc2_entry(jq[0][1], dead, n_in, oob), 1)
+  EMC2_A_LOAD(emc2_entry(jq[0][2], dead, n_in, oob), 2)
   __syncthreads();
 
   for (int g = 0; g < 9; ++g) {
@@ -203,7 +204,7 @@ k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, c
       }
       // the freed register set takes the A operands of tap + 3 (entries of "group 9" do not exist)
       const int32_t past = g < 8 ? 0 : -1;
-      EMC2_A_LOAD(jq[1][kx] | dead | past, kx)
+      EMC2_A_LOAD(emc2_entry(jq[1][kx], dead | past, n_in, oob), kx)
       __builtin_amdgcn_wave_barrier();
       // weights of tap + 1: registers -> the other LDS buffer; the barrier publishes them and retires the
       // buffer just read
@@ -221,6 +222,7 @@ k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, c
 #undef EMC2_A_LOAD
 #undef EMC2_W_LOAD
 #undef EMC2_W_STORE
+  emc2_report_oob(oob, dev_flags);
 
   // epilogue: lane (m, q) holds column 16*j + m of rows 16*mt + 4*q + e.  Scale/shift/ReLU/convert in
   // registers, then each 16-row tile goes through LDS so that the global stores are whole 16-byte pieces.
@@ -262,12 +264,12 @@ k_spconv_direct(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, c
 
 template <int DT, int CIN, int COUT>
 void launch_direct(const void* d_in, const void* d_wp, const float* d_scale, const float* d_shift, int epilogue,
-                   const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, const void* d_zero_row, void* d_out,
-                   hipStream_t s) {
+                   const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+                   const void* d_zero_row, void* d_out, hipStream_t s) {
   const int64_t rows_per_block = kDWaves * 16 * DirectCfg<CIN, COUT>::MT;
   hipLaunchKernelGGL((k_spconv_direct<DT, CIN, COUT>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),
                      dim3(kDThreads), 0, s, (const uint16_t*)d_in, (const u32x4*)d_wp, d_scale, d_shift, epilogue, d_nbr,
-                     d_n_out, capacity_out, (const uint16_t*)d_zero_row, (uint16_t*)d_out);
+                     d_n_out, capacity_out, n_in, dev_flags, (const uint16_t*)d_zero_row, (uint16_t*)d_out);
 }
 
 }  // namespace
@@ -284,12 +286,12 @@ void emc2_spconv_direct_pack(const void* d_w, int cin, int cout, void* d_packed,
 
 void emc2_spconv_direct_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                                const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
-                               int64_t capacity_out, int cin, int cout, const void* d_zero_row, void* d_out,
-                               hipStream_t stream) {
+                               int64_t capacity_out, int32_t n_in, int32_t* dev_flags, int cin, int cout,
+                               const void* d_zero_row, void* d_out, hipStream_t stream) {
 #define CASE(DTV, CI, CO)                                                                                              \
   if (dtype == DTV && cin == CI && cout == CO) {                                                                       \
-    launch_direct<DTV, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, d_zero_row, d_out, \
-                               stream);                                                                                \
+    launch_direct<DTV, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags,  \
+                               d_zero_row, d_out, stream);                                                             \
     return;                                                                                                            \
   }
   CASE(EMC2_F16, 32, 32) CASE(EMC2_F16, 32, 64) CASE(EMC2_F16, 64, 32) CASE(EMC2_F16, 64, 64)

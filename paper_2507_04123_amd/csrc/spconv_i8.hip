@@ -72,7 +72,8 @@ template <int CIN, int COUT, int OUTQ>
 __global__ void __launch_bounds__(kQThreads, (QCfg<CIN, COUT>::MINW))
 k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const float* __restrict__ mul,
             const float* __restrict__ add, int relu, float inv_out_scale, const int32_t* __restrict__ nbr,
-            const int32_t* __restrict__ d_n_out, int64_t capacity_out, const int8_t* __restrict__ zrow, void* __restrict__ out) {
+            const int32_t* __restrict__ d_n_out, int64_t capacity_out, int32_t n_in, int32_t* __restrict__ dev_flags,
+            const int8_t* __restrict__ zrow, void* __restrict__ out) {
   constexpr int KS = CIN / 64;                // k-steps per tap
   constexpr int NT = COUT / 16;               // 16-column tiles
   constexpr int MT = 4;                       // 16-row tiles per wave
@@ -106,6 +107,7 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
   const bool live = wave_row0 + lane < n_out;
   const int32_t* nrow = nbr + (live ? wave_row0 + lane : 0);
   const int32_t dead = live ? 0 : -1;   // OR-ed into kernel-map entries: rows past n_out have no neighbours
+  unsigned long long oob = 0ull;        // lanes that saw an entry outside [0, n_in)
 
   intx4 acc[MT][NT];
 #pragma unroll
@@ -154,9 +156,9 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
   EMC2_W_STORE(0, 0)
   EMC2_W_LOAD(1, 1)
   EMC2_W_LOAD(2, 2)
-  EMC2_A_LOAD(jq[0][0] | dead, 0)
-  EMC2_A_LOAD(jq[0][1] | dead, 1)
-  EMC2_A_LOAD(jq[0][2] | dead, 2)
+  EMC2_A_LOAD(emc2_entry(jq[0][0], dead, n_in, oob), 0)
+  EMC2_A_LOAD(emc2_entry(jq[0][1], dead, n_in, oob), 1)
+  EMC2_A_LOAD(emc2_entry(jq[0][2], dead, n_in, oob), 2)
   __syncthreads();
 
   for (int g = 0; g < 9; ++g) {
@@ -183,7 +185,7 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
       }
       // the freed register set takes the A operands of tap + 3 (entries of "group 9" do not exist)
       const int32_t past = g < 8 ? 0 : -1;
-      EMC2_A_LOAD(jq[1][kx] | dead | past, kx)
+      EMC2_A_LOAD(emc2_entry(jq[1][kx], dead | past, n_in, oob), kx)
       __builtin_amdgcn_wave_barrier();
       // weights of tap + 1: registers -> the other LDS buffer; the barrier publishes them and retires the one just read
       EMC2_W_STORE((tap + 1) & 1, (kx + 1) % 3)
@@ -200,6 +202,7 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
 #undef EMC2_A_LOAD
 #undef EMC2_W_LOAD
 #undef EMC2_W_STORE
+  emc2_report_oob(oob, dev_flags);
 
   // epilogue: lane (m, q) holds column 16*j + m of rows 16*mt + 4*q + e.  int -> fp32, multiply, add (each rounded
   // on its own), ReLU, convert; each 16-row tile goes through LDS so that global stores are whole 16-byte pieces.
@@ -244,12 +247,12 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
 
 template <int CIN, int COUT, int OUTQ>
 void launch_i8(const void* d_in, const void* d_wp, const float* d_mul, const float* d_add, int relu, float inv_out_scale,
-               const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, const void* d_zero_row, void* d_out,
-               hipStream_t s) {
+               const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+               const void* d_zero_row, void* d_out, hipStream_t s) {
   const int64_t rows_per_block = kQWaves * 64;
   hipLaunchKernelGGL((k_spconv_i8<CIN, COUT, OUTQ>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),
                      dim3(kQThreads), 0, s, (const int8_t*)d_in, (const u32x4*)d_wp, d_mul, d_add, relu, inv_out_scale, d_nbr,
-                     d_n_out, capacity_out, (const int8_t*)d_zero_row, d_out);
+                     d_n_out, capacity_out, n_in, dev_flags, (const int8_t*)d_zero_row, d_out);
 }
 
 bool i8_shape_ok(int cin, int cout) { return (cin == 64 || cin == 128) && (cout == 32 || cout == 64); }
@@ -286,12 +289,16 @@ extern "C" emc2_status emc2_pack_weights_i8(emc2_ctx* ctx, const int8_t* d_w, in
 
 extern "C" emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const void* d_w_packed, const float* d_mul,
                                       const float* d_add, int32_t relu, emc2_dtype out_dtype, float inv_out_scale,
-                                      const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t cin,
-                                      int32_t cout, void* d_out, void* stream) {
+                                      const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows,
+                                      int32_t cin, int32_t cout, void* d_out, void* stream) {
   if (!ctx) return EMC2_ERR_INVALID_ARG;
   if (!d_in || !d_w_packed || !d_mul || !d_add || !d_nbr || !d_n_out || !d_out)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_i8: null argument");
   if (capacity_out < 1) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_i8: capacity_out < 1");
+  if (n_in_rows < 0) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_i8: n_in_rows < 0");
+  if (((uintptr_t)d_in | (uintptr_t)d_w_packed | (uintptr_t)d_out) & 15u)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_i8: d_in, d_w_packed and d_out must be 16-byte aligned");
+  const int32_t n_in = n_in_rows > 0x7fffffff ? 0x7fffffff : (int32_t)n_in_rows;
   if (!i8_shape_ok(cin, cout))
     return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv_i8: Cin must be 64 or 128 and Cout 32 or 64");
   if (out_dtype != EMC2_I8 && out_dtype != EMC2_F16)
@@ -303,11 +310,11 @@ extern "C" emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const v
 #define CASE(CI, CO)                                                                                                        \
   if (cin == CI && cout == CO) {                                                                                            \
     if (out_dtype == EMC2_I8)                                                                                               \
-      launch_i8<CI, CO, 1>(d_in, d_w_packed, d_mul, d_add, rl, inv_out_scale, d_nbr, d_n_out, capacity_out, ctx->zero_row,  \
-                           d_out, s);                                                                                       \
+      launch_i8<CI, CO, 1>(d_in, d_w_packed, d_mul, d_add, rl, inv_out_scale, d_nbr, d_n_out, capacity_out, n_in,           \
+                           ctx->dev_words, ctx->zero_row, d_out, s);                                                        \
     else                                                                                                                    \
-      launch_i8<CI, CO, 0>(d_in, d_w_packed, d_mul, d_add, rl, inv_out_scale, d_nbr, d_n_out, capacity_out, ctx->zero_row,  \
-                           d_out, s);                                                                                       \
+      launch_i8<CI, CO, 0>(d_in, d_w_packed, d_mul, d_add, rl, inv_out_scale, d_nbr, d_n_out, capacity_out, n_in,           \
+                           ctx->dev_words, ctx->zero_row, d_out, s);                                                        \
   }
   CASE(64, 32) CASE(64, 64) CASE(128, 32) CASE(128, 64)
 #undef CASE

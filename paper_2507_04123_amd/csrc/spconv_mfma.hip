@@ -98,6 +98,7 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
                                                           const float* __restrict__ scale, const float* __restrict__ shift,
                                                           int epilogue, const int32_t* __restrict__ nbr,
                                                           const int32_t* __restrict__ d_n_out, int64_t capacity_out,
+                                                          int32_t n_in, int32_t* __restrict__ dev_flags,
                                                           uint16_t* __restrict__ out) {
   static_assert(MT == 2, "a wave owns 64 rows: one kernel-map entry per lane and tap");
   constexpr int KS = CIN / 16;                // k-steps per tap
@@ -150,6 +151,7 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
   const bool live = wave_row0 + lane < n_out;
   const int32_t* nrow = nbr + (live ? wave_row0 + lane : 0);
   const int32_t dead = live ? 0 : -1;   // OR-ed into kernel-map entries: rows past n_out have no neighbours
+  unsigned long long oob = 0ull;        // lanes that saw an entry outside [0, n_in)
   const int srow = lane / CH, schunk = lane % CH;   // staging role: row within an instruction, 16-byte chunk
 
   floatx16 acc[MT][NT];
@@ -202,10 +204,10 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
     EMC2_W_LOAD(1, 1)
     EMC2_W_LOAD(2, 2)
   }
-  EMC2_STAGE_LOAD(jq[0][0] | dead, 0)
+  EMC2_STAGE_LOAD(emc2_entry(jq[0][0], dead, n_in, oob), 0)
   if constexpr (D == 3) {
-    EMC2_STAGE_LOAD(jq[0][1] | dead, 1)
-    EMC2_STAGE_LOAD(jq[0][2] | dead, 2)
+    EMC2_STAGE_LOAD(emc2_entry(jq[0][1], dead, n_in, oob), 1)
+    EMC2_STAGE_LOAD(emc2_entry(jq[0][2], dead, n_in, oob), 2)
   }
   __syncthreads();
 
@@ -218,7 +220,7 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) {
       const int tap = 3 * g + kx;
-      const unsigned long long mask = __ballot((jq[0][kx] | dead) >= 0);
+      const unsigned long long mask = __ballot(emc2_entry(jq[0][kx], dead, n_in, oob) >= 0);
       // weights of tap + WD: global -> registers (the set was emptied at the end of the previous tap)
       EMC2_W_LOAD(tap + WD < 27 ? tap + WD : 26, kx % WD)
       // gathered rows of this tap: registers -> wave-private LDS tile
@@ -231,9 +233,9 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
       // the freed register set takes the gather of tap + D (absent entries re-read row 0 and are masked)
       const int32_t past = g < 8 ? 0 : -1;   // entries of "group 9" do not exist
       if constexpr (D == 3) {
-        EMC2_STAGE_LOAD(jq[1][kx] | dead | past, kx)
+        EMC2_STAGE_LOAD(emc2_entry(jq[1][kx], dead | past, n_in, oob), kx)
       } else {
-        if (kx < 2) { EMC2_STAGE_LOAD(jq[0][kx < 2 ? kx + 1 : 0] | dead, 0) } else { EMC2_STAGE_LOAD(jq[1][0] | dead | past, 0) }
+        if (kx < 2) { EMC2_STAGE_LOAD(emc2_entry(jq[0][kx < 2 ? kx + 1 : 0], dead, n_in, oob), 0) } else { EMC2_STAGE_LOAD(emc2_entry(jq[1][0], dead | past, n_in, oob), 0) }
       }
       __builtin_amdgcn_wave_barrier();
       const u32x4* wb = wl[tap % NB];
@@ -276,6 +278,7 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
 #undef EMC2_STAGE_LOAD
 #undef EMC2_W_LOAD
 #undef EMC2_W_STORE
+  emc2_report_oob(oob, dev_flags);
 
   // epilogue: lane holds column n = 32*j + m; acc element e <-> row 8*(e/4) + 4*h + (e%4).
   // Scale/shift/ReLU/convert in registers, then each 32-row tile goes through the wave's LDS tile so that
@@ -318,22 +321,23 @@ __global__ void __launch_bounds__(kThreads, (Pipe<CIN, COUT>::MINW)) k_spconv_mf
 
 template <int DT, int CIN, int COUT>
 void launch(const void* d_in, const void* d_wp, const float* d_scale, const float* d_shift, int epilogue,
-            const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, void* d_out, hipStream_t s) {
+            const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+            void* d_out, hipStream_t s) {
   constexpr int MT = 2;
   const int64_t rows_per_block = kWaves * MT * 32;
   hipLaunchKernelGGL((k_spconv_mfma<DT, CIN, COUT, MT>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),  // + 8: the per-XCD ranges round up
-                    
                      dim3(kThreads), 0, s, (const uint16_t*)d_in, (const u32x4*)d_wp, d_scale, d_shift, epilogue, d_nbr,
-                     d_n_out, capacity_out, (uint16_t*)d_out);
+                     d_n_out, capacity_out, n_in, dev_flags, (uint16_t*)d_out);
 }
 
 template <int DT>
 void dispatch(const void* d_in, const void* d_wp, const float* d_scale, const float* d_shift, int epilogue,
-              const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int cin, int cout, void* d_out,
-              hipStream_t s) {
+              const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags, int cin,
+              int cout, void* d_out, hipStream_t s) {
 #define CASE(CI, CO)                                                                                              \
   if (cin == CI && cout == CO) {                                                                                  \
-    launch<DT, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, d_out, s);           \
+    launch<DT, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags,     \
+                       d_out, s);                                                                                 \
     return;                                                                                                       \
   }
   CASE(16, 32) CASE(32, 32) CASE(32, 64) CASE(64, 64) CASE(64, 128) CASE(128, 128)
@@ -357,9 +361,12 @@ void emc2_spconv_mfma_pack(const void* d_w, int cin, int cout, void* d_packed, h
 
 void emc2_spconv_mfma_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                              const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
-                             int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream) {
+                             int64_t capacity_out, int32_t n_in, int32_t* dev_flags, int cin, int cout, void* d_out,
+                             hipStream_t stream) {
   if (dtype == EMC2_F16)
-    dispatch<EMC2_F16>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, stream);
+    dispatch<EMC2_F16>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags, cin, cout,
+                       d_out, stream);
   else
-    dispatch<EMC2_BF16>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, cin, cout, d_out, stream);
+    dispatch<EMC2_BF16>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags, cin, cout,
+                        d_out, stream);
 }

@@ -73,9 +73,9 @@ __device__ __forceinline__ GroupInfo analyze(const int32_t j[3]) {
   for (int kx = 0; kx < 3; ++kx) {
     const unsigned long long mk = __ballot(j[kx] >= 0);
     gi.valid[kx] = mk;
-    // the table is ascending in the row index wherever it is valid, so the first and last valid lanes hold
-    // the extremes; a table that is not ascending merely fails the range check below and takes the
-    // three-pass route
+    // a table from emc2_build_kmap is ascending in the row index wherever it is valid, so the first and last
+    // valid lanes hold the extremes; in any other table some entry falls outside [lo, hi], fails the range
+    // check below, and the group takes the three-pass route
     const int first = mk ? __builtin_ctzll(mk) : 0;
     const int last = mk ? 63 - __builtin_clzll(mk) : 0;
     const int32_t vf = __builtin_amdgcn_readlane(j[kx], first);
@@ -86,11 +86,15 @@ __device__ __forceinline__ GroupInfo analyze(const int32_t j[3]) {
     }
   }
   if (lo == 0x7fffffff) lo = 0;
-  unsigned long long bad = 0ull;
+  if (hi < lo) hi = lo;
+  // rows past hi are not fetched (the gather clamps to hi), so an entry is usable in span mode only inside
+  // [lo, hi], and the interval must fit the tile
+  const uint32_t width = (uint32_t)(hi - lo);
+  unsigned long long bad = width >= (uint32_t)SMAX ? ~0ull : 0ull;
 #pragma unroll
-  for (int kx = 0; kx < 3; ++kx) bad |= __ballot(j[kx] >= 0 && (uint32_t)(j[kx] - lo) >= (uint32_t)SMAX);
+  for (int kx = 0; kx < 3; ++kx) bad |= __ballot(j[kx] >= 0 && (uint32_t)(j[kx] - lo) > width);
   gi.lo = lo;
-  gi.hi = hi < lo ? lo : hi;
+  gi.hi = hi;
   gi.span = bad == 0ull;
   return gi;
 }
@@ -104,6 +108,7 @@ template <int DT, int CIN, int COUT, bool LATE>
 __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp,
                                           const float* __restrict__ scale, const float* __restrict__ shift, int epilogue,
                                           const int32_t* __restrict__ nbr, int64_t n_out, int64_t capacity_out,
+                                          int32_t n_in, int32_t* __restrict__ dev_flags,
                                           uint16_t* __restrict__ out, u32x4* __restrict__ wl, u32x4* __restrict__ my_tile,
                                           int64_t wave_row0) {
   constexpr int KS = CIN / 32;                // k-steps per tap (v_mfma_f32_16x16x32)
@@ -127,6 +132,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   const bool live = wave_row0 + lane < n_out;
   const int32_t* nrow = nbr + (live ? wave_row0 + lane : 0);
   const int32_t dead = live ? 0 : -1;               // rows past n_out have no neighbours
+  unsigned long long oob = 0ull;                    // lanes that saw an entry outside [0, n_in)
   const int srow = lane / CH, schunk = lane % CH;   // gather role: row within an instruction, 16-byte chunk
 
   floatx4 acc[MT][NT];
@@ -145,7 +151,9 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 #define EMC2_IDX_LOAD(GROUP, DST)                                                                          \
   _Pragma("unroll") for (int kx_ = 0; kx_ < 3; ++kx_)                                                      \
       DST[kx_] = nrow[(int64_t)(3 * ((GROUP) < 9 ? (GROUP) : 8) + kx_) * capacity_out];
-#define EMC2_MASKED(C, J) const int32_t C[3] = {J[0] | dead, J[1] | dead, J[2] | dead};
+#define EMC2_MASKED(C, J)                                                                                  \
+  const int32_t C[3] = {emc2_entry(J[0], dead, n_in, oob), emc2_entry(J[1], dead, n_in, oob),              \
+                        emc2_entry(J[2], dead, n_in, oob)};
 #define EMC2_W_LOAD(GROUP)                                                                                 \
   {                                                                                                        \
     const u32x4* wsrc_ = wp + (int64_t)((GROUP) < 9 ? (GROUP) : 8) * G16;                                  \
@@ -312,6 +320,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 #undef EMC2_TAP
 #undef EMC2_LROW
 #undef EMC2_COMPUTE
+  emc2_report_oob(oob, dev_flags);
 
   // epilogue: lane (m, q) holds column 16*j + m of rows 16*mt + 4*q + e.  Scale/shift/ReLU/convert in
   // registers, then each 16-row tile goes through the wave's LDS tile so that the global stores are whole
@@ -359,7 +368,8 @@ template <int DT, int CIN, int COUT>
 __global__ void __launch_bounds__(kSpanThreads, (SpanCfg<CIN>::MINW))
 k_spconv_span(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, const float* __restrict__ scale,
               const float* __restrict__ shift, int epilogue, const int32_t* __restrict__ nbr,
-              const int32_t* __restrict__ d_n_out, int64_t capacity_out, uint16_t* __restrict__ out) {
+              const int32_t* __restrict__ d_n_out, int64_t capacity_out, int32_t n_in, int32_t* __restrict__ dev_flags,
+              uint16_t* __restrict__ out) {
   constexpr int G16 = 3 * (CIN / 32) * (COUT / 16) * 64;
   constexpr int SMAX = SpanCfg<CIN>::SMAX;
   constexpr int ROW16 = CIN / 8 + 1;
@@ -379,18 +389,21 @@ k_spconv_span(const uint16_t* __restrict__ in, const u32x4* __restrict__ wp, con
   const int64_t wave_row0 = tile_id * (kSpanWaves * 64) + (int64_t)wave * 64;
   // waves w and w + 4 share a SIMD: one of each kind per SIMD
   if (wave < 4)
-    span_wave<DT, CIN, COUT, false>(in, wp, scale, shift, epilogue, nbr, n_out, capacity_out, out, wl, tile[wave], wave_row0);
+    span_wave<DT, CIN, COUT, false>(in, wp, scale, shift, epilogue, nbr, n_out, capacity_out, n_in, dev_flags, out, wl,
+                                    tile[wave], wave_row0);
   else
-    span_wave<DT, CIN, COUT, true>(in, wp, scale, shift, epilogue, nbr, n_out, capacity_out, out, wl, tile[wave], wave_row0);
+    span_wave<DT, CIN, COUT, true>(in, wp, scale, shift, epilogue, nbr, n_out, capacity_out, n_in, dev_flags, out, wl,
+                                    tile[wave], wave_row0);
 }
 
 template <int DT, int CIN, int COUT>
 void launch_span(const void* d_in, const void* d_wp, const float* d_scale, const float* d_shift, int epilogue,
-                 const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, void* d_out, hipStream_t s) {
+                 const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+                 void* d_out, hipStream_t s) {
   const int64_t rows_per_block = kSpanWaves * 64;
   hipLaunchKernelGGL((k_spconv_span<DT, CIN, COUT>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),
                      dim3(kSpanThreads), 0, s, (const uint16_t*)d_in, (const u32x4*)d_wp, d_scale, d_shift, epilogue, d_nbr,
-                     d_n_out, capacity_out, (uint16_t*)d_out);
+                     d_n_out, capacity_out, n_in, dev_flags, (uint16_t*)d_out);
 }
 
 }  // namespace
@@ -402,10 +415,12 @@ bool emc2_spconv_span_supported(int cin, int cout) { return cin == 64 && cout ==
 
 void emc2_spconv_span_launch(emc2_dtype dtype, const void* d_in, const void* d_wp, const float* d_scale,
                              const float* d_shift, int epilogue, const int32_t* d_nbr, const int32_t* d_n_out,
-                             int64_t capacity_out, int cin, int cout, void* d_out, hipStream_t stream) {
+                             int64_t capacity_out, int32_t n_in, int32_t* dev_flags, int cin, int cout, void* d_out,
+                             hipStream_t stream) {
 #define CASE(DTV, CI, CO)                                                                                           \
   if (dtype == DTV && cin == CI && cout == CO) {                                                                    \
-    launch_span<DTV, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, d_out, stream);  \
+    launch_span<DTV, CI, CO>(d_in, d_wp, d_scale, d_shift, epilogue, d_nbr, d_n_out, capacity_out, n_in, dev_flags, \
+                             d_out, stream);                                                                        \
     return;                                                                                                         \
   }
   CASE(EMC2_F16, 64, 64) CASE(EMC2_BF16, 64, 64)

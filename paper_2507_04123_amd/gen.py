@@ -279,7 +279,11 @@ def make_proposals(n_scenes: int, seed: int, dist: float = 23.5, conf: float = 0
     """Proposal regions of `n_scenes` driving scenes: props[N][4] float32 (x, y, z, confidence) and scene[N] int32,
     shuffled.  A third of the scenes hold only near, confidently detected objects, a third add a few that are
     near but unclear or far but clear, a third also some that are far and unclear (confidence falls with range,
-    as sparse returns make distant objects hard); a few scenes are empty."""
+    as sparse returns make distant objects hard); a few scenes are empty.  About one proposal in fifty sits on a
+    threshold: at range exactly `dist`, one float below it, or at `dist` in a slanted direction (where the
+    squared range is decided by how the two products round), and with confidence exactly `conf` or one float
+    beside it -- always on the side that keeps the scene in its third, so the mix of experts stays balanced
+    while every comparison is exercised at its edge."""
     st = Stream(seed, 5000)
     kinds = (st.bits(n_scenes) % np.uint64(3)).astype(np.int64)
     sizes = (st.bits(n_scenes) % np.uint64(max_per_scene + 1)).astype(np.int64)
@@ -302,7 +306,29 @@ def make_proposals(n_scenes: int, seed: int, dist: float = 23.5, conf: float = 0
             r = np.where(both, st.uniform(k, 1.02 * dist, 3.0 * dist), r)
             c = np.where(both, st.uniform(k, 0.0, max(conf - 0.05, 0.0)), c)
         z = st.uniform(k, -1.6, 0.4)
-        props.append(np.stack([r * np.cos(a), r * np.sin(a), z, c], axis=1))
+        rows = np.stack([r * np.cos(a), r * np.sin(a), z, c], axis=1).astype(np.float32)
+        # threshold cases (float32 values placed after the rounding above)
+        d32, c32 = np.float32(dist), np.float32(conf)
+        d_below, c_above, c_below = np.nextafter(d32, np.float32(0)), np.nextafter(c32, np.float32(2)), np.nextafter(c32, np.float32(-1))
+        n_edge = max(1, k // 50)
+        which = (st.bits(n_edge) % np.uint64(4)).astype(np.int64)
+        axis = (st.bits(n_edge) % np.uint64(4)).astype(np.int64)      # +x, -x, +y, -y
+        slant = st.uniform(n_edge, -1.5, 1.5)
+        for e in range(n_edge):
+            if kinds[s] == 0:        # stays near and clear: one float inside the distance, at or just above the confidence
+                rr, cc = d_below, (c32 if which[e] % 2 == 0 else c_above)
+            elif kinds[s] == 1:      # far but clear (range exactly on the threshold), or near but just unclear
+                rr, cc = (d32, c_above) if which[e] % 2 == 0 else (d_below, c_below)
+            else:                    # far and just unclear
+                rr, cc = d32, c_below
+            if kinds[s] >= 1 and which[e] >= 2 and rr == d32:
+                # slanted direction: x^2 + y^2 lands within a few floats of dist^2, on either side; the scene is in
+                # the versatile or accuracy third either way, and both sides must decide it by the same roundings
+                xy = (np.float32(dist * math.cos(slant[e])), np.float32(dist * math.sin(slant[e])))
+            else:
+                xy = [(rr, 0.0), (-rr, 0.0), (0.0, rr), (0.0, -rr)][axis[e]]
+            rows[e] = (xy[0], xy[1], rows[e, 2], cc)
+        props.append(rows)
         scenes.append(np.full(k, s, np.int64))
     if not props:
         return np.zeros((0, 4), np.float32), np.zeros((0,), np.int32)

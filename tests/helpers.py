@@ -1,6 +1,7 @@
 """Shared test helpers: the oracle-side chain of a workload branch and the feature tolerance."""
 from __future__ import annotations
 
+import os
 from typing import Dict, List, Tuple
 
 import numpy as np
@@ -26,6 +27,31 @@ def assert_features_close(got: np.ndarray, exp: np.ndarray, rtol: float, what: s
         i = np.unravel_index(np.argmax(err - bound), err.shape)
         raise AssertionError(f"{what}: {int(bad.sum())}/{exp.size} elements outside rtol={rtol}; worst at {i}: "
                              f"got {got[i]!r} exp {exp[i]!r} rms {rms:.4g}")
+
+
+_PROGRESS_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "pytest_progress.log")
+
+
+def progress(msg: str) -> None:
+    """A progress line of a long test: printed, and appended to a log file a job monitor can watch (pytest holds
+    back what a passing test prints)."""
+    print(msg, flush=True)
+    try:
+        os.makedirs(os.path.dirname(_PROGRESS_LOG), exist_ok=True)
+        with open(_PROGRESS_LOG, "a") as f:
+            f.write(msg + "\n")
+    except OSError:
+        pass
+
+
+def worst_feature_ratio(got: np.ndarray, exp: np.ndarray) -> float:
+    """max |g - o| / (|o| + rms(o)): the smallest rtol at which assert_features_close would pass."""
+    got = np.asarray(got, dtype=np.float64)
+    exp = np.asarray(exp, dtype=np.float64)
+    if exp.size == 0:
+        return 0.0
+    rms = float(np.sqrt(np.mean(exp * exp)))
+    return float(np.max(np.abs(got - exp) / (np.abs(exp) + rms)))
 
 
 def layer_params_host(branch: Branch, seed: int, dtype: int) -> List[Dict[str, np.ndarray]]:

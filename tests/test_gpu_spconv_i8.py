@@ -142,3 +142,33 @@ def test_spconv_i8_rejects_unsupported():
     with pytest.raises(B.Emc2Error):
         ctx.pack_weights_i8(torch.zeros((27, 48, 64), dtype=torch.int8, device="cuda"), torch.zeros(27 * 48 * 64, dtype=torch.int8, device="cuda"))
     ctx.close()
+
+
+def test_spconv_i8_entries_beyond_the_input_are_refused():
+    """As for the 16-bit conv: an entry at or beyond n_in_rows reads nothing and is reported through the status word."""
+    ctx = B.Context(16, 4096, 64 * 64 * 8, n_slots=1)
+    cin, cout, n_in, n_out, slack = 64, 64, 200, 333, 30
+    st = gen.Stream(515, 2)
+    xq = (st.bits((n_in + slack) * cin) % np.uint64(255)).astype(np.int64).astype(np.int32) - 127
+    xq = xq.astype(np.int8).reshape(-1, cin)
+    wq = ((st.bits(27 * cin * cout) % np.uint64(121)).astype(np.int32) - 60).astype(np.int8).reshape(27, cin, cout)
+    mul = st.uniform(cout, 1e-5, 3e-5).astype(np.float32)
+    add = st.uniform(cout, -0.1, 0.1).astype(np.float32)
+    bad = (st.bits(27 * n_out) % np.uint64(n_in + slack)).astype(np.int32).reshape(27, n_out)
+    bad[st.uniform(27 * n_out, 0.0, 1.0).reshape(27, n_out) < 0.5] = -1
+    bad[5, 64] = n_in
+    cleaned = np.where(bad >= n_in, -1, bad).astype(np.int32)
+    ov, oq = oracle.spconv_i8(xq[:n_in], wq, mul, add, True, cleaned, inv_out_scale=25.0)
+    wp = torch.empty((27 * cin * cout,), dtype=torch.int8, device="cuda")
+    ctx.pack_weights_i8(dev(wq), wp)
+    out = torch.zeros((n_out, cout), dtype=torch.int8, device="cuda")
+    n_t = torch.tensor([n_out], dtype=torch.int32, device="cuda")
+    print("spconv_i8 refused entries", flush=True)
+    ctx.spconv_i8(dev(xq), wp, cin, cout, dev(mul), dev(add), True, dev(bad), n_t, n_out, out, inv_out_scale=25.0, n_in_rows=n_in)
+    with pytest.raises(B.Emc2Error) as ei:
+        ctx.status_sync()
+    assert ei.value.status == B.ERR_MAP
+    assert np.array_equal(out.cpu().numpy(), oq)
+    ctx.spconv_i8(dev(xq), wp, cin, cout, dev(mul), dev(add), True, dev(cleaned), n_t, n_out, out, inv_out_scale=25.0, n_in_rows=n_in)
+    ctx.status_sync()
+    ctx.close()

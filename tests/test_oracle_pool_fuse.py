@@ -247,3 +247,73 @@ def test_pool_then_fuse_on_a_scene():
     assert len(coords) == len(lc) + len(ic) - int(((sl >= 0) & (si >= 0)).sum())
     assert np.array_equal(feats[sl >= 0, :4], lf) and np.array_equal(feats[si >= 0, 4:], if_)
     assert not feats[sl < 0, :4].any() and not feats[si < 0, 4:].any()
+
+
+# ------------------------------------------------------------------------------------------------
+# the rounding of the lift itself (fp64, left to right, one rounding to fp32), with exact rationals
+# ------------------------------------------------------------------------------------------------
+
+def _lift_exact_rational(qrow, d, i, j):
+    """One row of Q (d*u, d*v, d, 1) as the reading fixes it -- every product and every sum rounded to fp64 on
+    its own, in the order written, then one rounding to fp32 -- evaluated with exact rationals: float(Fraction)
+    is the correctly rounded fp64 value, so no floating-point product or sum of the platform enters."""
+    from fractions import Fraction as Fr
+    r64 = lambda fr: Fr(float(fr))                                  # round to nearest even fp64
+    du, dv = r64(Fr(float(d)) * i), r64(Fr(float(d)) * j)
+    t = r64(Fr(float(qrow[0])) * du)
+    t = r64(t + r64(Fr(float(qrow[1])) * dv))
+    t = r64(t + r64(Fr(float(qrow[2])) * Fr(float(d))))
+    t = r64(t + Fr(float(qrow[3])))
+    return np.float32(float(t))                                     # fp64 -> fp32, nearest even
+
+
+def _lift_all_fp32(qrow, d, i, j):
+    """The same row with every operation rounded to fp32: the evaluation a single-precision kernel would do."""
+    f = np.float32
+    du, dv = f(d) * f(i), f(d) * f(j)
+    return f(f(f(f(qrow[0]) * du) + f(f(qrow[1]) * dv)) + f(f(qrow[2]) * f(d))) + f(qrow[3])
+
+
+def test_lift_rounding_is_fp64_then_one_fp32_rounding():
+    """Pins the lift's rounding bit for bit.  On a small image every lifted coordinate equals the exact-rational
+    evaluation of the reading; among them are pixels where an all-fp32 evaluation gives another float, and for
+    those a grid is laid so that the two floats fall into different cells: the pooled cell is the reading's."""
+    h, w = 24, 40
+    pm = gen.make_camera(77)
+    qm = gen.make_unprojection(pm)
+    st = gen.Stream(2024, 5)
+    depth = st.uniform(h * w, 4.0, 60.0).astype(np.float32).reshape(h, w)
+    img = np.ones((h, w, 1), np.float32)
+    _, _, _, xyz = oracle.pool_image(img, depth, qm, (-100.0, -100.0, -100.0), (1.0, 1.0, 1.0), (200, 200, 200), want_xyz=True)
+    differing = []
+    for j in range(h):
+        for i in range(w):
+            for a in range(3):
+                want = _lift_exact_rational(qm[4 * a:4 * a + 4], depth[j, i], i, j)
+                assert xyz[j, i, a] == want, (j, i, a, xyz[j, i, a], want)
+                alt = _lift_all_fp32(qm[4 * a:4 * a + 4], depth[j, i], i, j)
+                if alt != want and abs(float(want)) > 1.0:
+                    differing.append((j, i, a, want, alt))
+    assert len(differing) >= 10, "the search found too few pixels on which the two roundings disagree"
+    checked = 0
+    for j, i, a, want, alt in differing[:40]:
+        # cells four ulps wide from a lower bound a few cells under both values: the bound and the cell size are
+        # fp32 numbers, and subtraction and division are exact in fp32 (all are multiples of the values' ulp and close
+        # together), so the two floats sit in different cells whenever they straddle a multiple of the cell size
+        vs = 4.0 * float(np.spacing(np.float32(min(abs(float(want)), abs(float(alt))))))
+        c_want, c_alt = int(np.floor(float(want) / vs)), int(np.floor(float(alt) / vs))
+        if c_want == c_alt:
+            continue
+        lo_a = (min(c_want, c_alt) - 3) * vs
+        if float(np.float32(lo_a)) != lo_a:
+            continue                                                # the bound left the values' binade
+        lo, vsz, grid = [-1000.0] * 3, [2000.0] * 3, [1, 1, 1]
+        lo[a], vsz[a], grid[a] = lo_a, vs, 64
+        one = np.zeros((h, w), np.float32)
+        one[j, i] = depth[j, i]                                     # only this pixel is relevant
+        coords, _, counts = oracle.pool_image(img, one, qm, lo, vsz, grid)
+        assert len(coords) == 1 and counts[0] == 1
+        assert coords[0][3 - a] == c_want - (min(c_want, c_alt) - 3), (j, i, a)      # columns are (b, z, y, x)
+        assert coords[0][3 - a] != c_alt - (min(c_want, c_alt) - 3)
+        checked += 1
+    assert checked >= 3, "no pixel separated the two roundings at the cell level"
