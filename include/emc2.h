@@ -68,7 +68,8 @@ void emc2_destroy(emc2_ctx* ctx);
  * and clear it. */
 emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream);
 
-/* Text of the last host-side error on this context (never NULL). */
+/* Text of the last host-side error on this context (never NULL); with ctx = NULL, of the last failed call
+ * that takes no context (emc2_build_kmap_static). */
 const char* emc2_last_error(const emc2_ctx* ctx);
 
 /* Voxel grid: the "pool size" is a runtime parameter (paper Sec. 3.5, Multiscale Pooling is
@@ -139,6 +140,28 @@ emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d
                             int32_t n_batch, int32_t in_slot, int32_t out_slot, int64_t capacity_out,
                             int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr,
                             int32_t grid_out[3], int32_t* h_n_out, void* stream);
+
+/*
+ * emc2_build_kmap for callers that cannot allocate device memory and therefore cannot hold a context: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operation, arguments and results
+ * as emc2_build_kmap with in_slot = out_slot = -1 (the cell index is rebuilt from d_in_coords, nothing is kept),
+ * but the scratch (two cell-index slots, scan partials, status word: about 8.4 MB) is a static device array that
+ * every GPU the library runs on holds until the process ends.  It allocates and frees nothing, on the host or
+ * on the device, and never synchronises.
+ *   - Works on the CURRENT device; d_* pointers must belong to it.
+ *   - n_batch*Gx*Gy*Gz of grid_in must not exceed EMC2_STATIC_KMAP_MAX_CELLS: EMC2_ERR_INVALID_ARG otherwise
+ *     (text through emc2_last_error(NULL)); larger grids need a context.
+ *   - d_status: device int32 that receives this call's status bits (0 = fine, bit 0 = more outputs than
+ *     capacity_out: results truncated but in bounds), or NULL to ignore them.
+ *   - Every call on a GPU shares that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ *     host threads) race and give wrong maps.  Issue them on one stream, or order them with events.
+ *   - The first call on a device also enqueues a one-time zero fill of the array on `stream`.
+ */
+#define EMC2_STATIC_KMAP_MAX_CELLS (1 << 24)
+emc2_status emc2_build_kmap_static(emc2_conv_kind kind, const int32_t* d_in_coords, const int32_t* d_n_in,
+                                   int64_t capacity_in, const int32_t grid_in[3], int32_t n_batch, int64_t capacity_out,
+                                   int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr, int32_t grid_out[3],
+                                   int32_t* d_status, void* stream);
 
 typedef enum { EMC2_EPI_NONE = 0, EMC2_EPI_AFFINE = 1, EMC2_EPI_AFFINE_RELU = 2 } emc2_epilogue;
 

@@ -30,7 +30,7 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
            "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch", "emc2_spconv_i8_supported",
-           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8"]
+           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8", "emc2_build_kmap_static"]
 
 
 class Emc2Error(RuntimeError):
@@ -71,6 +71,9 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_build_kmap.restype = ctypes.c_int
     lib.emc2_build_kmap.argtypes = [vp, ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i32, i32, i64, vp, vp, vp,
                                     ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+    lib.emc2_build_kmap_static.restype = ctypes.c_int
+    lib.emc2_build_kmap_static.argtypes = [ctypes.c_int, vp, vp, i64, ctypes.POINTER(i32), i32, i64, vp, vp, vp,
+                                           ctypes.POINTER(i32), vp, vp]
     lib.emc2_spconv.restype = ctypes.c_int
     lib.emc2_spconv.argtypes = [vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, i32, vp, i64, i64, i32, i32, vp, vp]
     lib.emc2_pack_weights.restype = ctypes.c_int
@@ -116,6 +119,38 @@ def _stream() -> ctypes.c_void_p:
 def _dev_check(t: torch.Tensor, dtype: torch.dtype, name: str) -> None:
     if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
         raise ValueError(f"{name}: need a contiguous {dtype} device tensor, got {t.dtype} on {t.device}")
+
+
+STATIC_KMAP_MAX_CELLS = 1 << 24
+
+
+def build_kmap_static(kind: int, in_coords: torch.Tensor, n_in: torch.Tensor, capacity_in: int, grid_in: Sequence[int],
+                      n_batch: int, capacity_out: int, nbr: torch.Tensor, n_out: torch.Tensor,
+                      out_coords: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> Tuple[int, int, int]:
+    """emc2_build_kmap_static: the kernel map without a context (static device scratch, nothing allocated), on the
+    current device and torch's current stream.  Returns the output grid."""
+    if not torch.cuda.is_available():
+        raise RuntimeError("emc2 needs a GPU: there is no CPU path")
+    lib = load_library()
+    _dev_check(in_coords, torch.int32, "in_coords")
+    _dev_check(n_in, torch.int32, "n_in")
+    _dev_check(nbr, torch.int32, "nbr")
+    _dev_check(n_out, torch.int32, "n_out")
+    if in_coords.numel() < 4 * capacity_in or nbr.numel() < 27 * capacity_out:
+        raise ValueError("buffers smaller than capacity")
+    if out_coords is not None:
+        _dev_check(out_coords, torch.int32, "out_coords")
+        if out_coords.numel() < 4 * capacity_out:
+            raise ValueError("out_coords smaller than capacity_out")
+    if status is not None:
+        _dev_check(status, torch.int32, "status")
+    g_in = (ctypes.c_int32 * 3)(*grid_in)
+    g_out = (ctypes.c_int32 * 3)()
+    st = lib.emc2_build_kmap_static(kind, _ptr(in_coords), _ptr(n_in), capacity_in, g_in, n_batch, capacity_out,
+                                    _ptr(out_coords), _ptr(n_out), _ptr(nbr), g_out, _ptr(status), _stream())
+    if st != OK:
+        raise Emc2Error(st, lib.emc2_last_error(None).decode())
+    return g_out[0], g_out[1], g_out[2]
 
 
 class Context:

@@ -119,4 +119,7 @@ void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t ca
 void emc2_index_mark_coords(emc2_ctx* ctx, cellword_t* idx, const int32_t* d_coords, const int32_t* d_n,
                             int64_t capacity, const int32_t grid[3], int32_t n_batch, hipStream_t stream);
 
+// text of the last host-side error of emc2_build_kmap_static (kmap.hip); what emc2_last_error(NULL) returns
+const char* emc2_static_last_error();
+
 static inline int64_t emc2_div_up(int64_t a, int64_t b) { return (a + b - 1) / b; }

@@ -134,4 +134,4 @@ extern "C" emc2_status emc2_status_sync(emc2_ctx* ctx, void* stream) {
   return EMC2_OK;
 }
 
-extern "C" const char* emc2_last_error(const emc2_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+extern "C" const char* emc2_last_error(const emc2_ctx* ctx) { return ctx ? ctx->err : emc2_static_last_error(); }

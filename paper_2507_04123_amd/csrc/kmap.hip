@@ -6,6 +6,12 @@
 //          3x3x3 window contains one of its voxels in the output cell index; the scan ranks them
 //          (= ascending key order); the set bits are expanded to coordinates; then every output
 //          probes the input index at 2*o - 1 + k.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+
 #include "common.h"
 
 namespace {
@@ -175,14 +181,12 @@ __global__ void __launch_bounds__(256) k_copy_coords(const int4* __restrict__ sr
   if (i < n) dst[i] = src[i];
 }
 
-}  // namespace
-
-extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_in_coords,
-                                       const int32_t* d_n_in, int64_t capacity_in, const int32_t grid_in[3],
-                                       int32_t n_batch, int32_t in_slot, int32_t out_slot, int64_t capacity_out,
-                                       int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr, int32_t grid_out[3],
-                                       int32_t* h_n_out, void* stream) {
-  if (!ctx) return EMC2_ERR_INVALID_ARG;
+// The whole call, on whatever context it is given: one made by emc2_create, or the per-device one whose scratch
+// is the static array further down.
+emc2_status build_kmap_on(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_in_coords, const int32_t* d_n_in,
+                          int64_t capacity_in, const int32_t grid_in[3], int32_t n_batch, int32_t in_slot, int32_t out_slot,
+                          int64_t capacity_out, int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr, int32_t grid_out[3],
+                          int32_t* h_n_out, void* stream) {
   if (kind != EMC2_CONV_SUBM && kind != EMC2_CONV_STRIDED)
     return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_build_kmap: bad kind");
   if (!d_in_coords || !d_n_in || !grid_in || !d_n_out || !d_nbr || !grid_out)
@@ -269,6 +273,135 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
     st = emc2_check_hip(ctx, hipStreamSynchronize(s), "hipStreamSynchronize");
     if (st != EMC2_OK) return st;
     *h_n_out = ctx->pinned[2];
+  }
+  return EMC2_OK;
+}
+
+}  // namespace
+
+extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_in_coords,
+                                       const int32_t* d_n_in, int64_t capacity_in, const int32_t grid_in[3],
+                                       int32_t n_batch, int32_t in_slot, int32_t out_slot, int64_t capacity_out,
+                                       int32_t* d_out_coords, int32_t* d_n_out, int32_t* d_nbr, int32_t grid_out[3],
+                                       int32_t* h_n_out, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  return build_kmap_on(ctx, kind, d_in_coords, d_n_in, capacity_in, grid_in, n_batch, in_slot, out_slot, capacity_out,
+                       d_out_coords, d_n_out, d_nbr, grid_out, h_n_out, stream);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// emc2_build_kmap_static: the same call for callers that must not allocate.  Everything emc2_build_kmap keeps in
+// a context's scratch (two cell-index slots with their tile flags, the scan's partial sums, the status and
+// count words) lives in one file-scope device array instead; each GPU holds its own copy at its own address,
+// looked up once per device, and a host-side context structure per device points into it.
+// ---------------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int64_t kStaticMaxCells = EMC2_STATIC_KMAP_MAX_CELLS;
+constexpr int64_t kStaticTiles = (kStaticMaxCells / 32 + 1 + EMC2_SCAN_TILE - 1) / EMC2_SCAN_TILE;   // as emc2_create sizes a slot
+constexpr int64_t kStaticWords = kStaticTiles * EMC2_SCAN_TILE;
+constexpr size_t kStaticSlotBytes = sizeof(cellword_t) * (size_t)kStaticWords + sizeof(uint32_t) * (size_t)kStaticTiles;
+constexpr size_t kStaticSlotPitch = (kStaticSlotBytes + 255) / 256 * 256;
+constexpr size_t kStaticPartialsBytes = ((size_t)(kStaticTiles + 1) * sizeof(uint32_t) + 255) / 256 * 256;
+constexpr size_t kStaticBytes = 2 * kStaticSlotPitch + kStaticPartialsBytes + 256;   // + status / count words
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kStaticMaxDevices = 64;
+struct StaticKmap {
+  bool ready;
+  unsigned char* ptr;        // this device's address of `scratch`
+  emc2_ctx ctx;              // host-side view of the scratch: no device memory of its own
+  cellword_t* slots[2];
+  SlotMeta meta[2];
+};
+StaticKmap g_static[kStaticMaxDevices];
+std::mutex g_static_mutex;
+char g_static_err[256] = "";
+
+emc2_status static_fail(emc2_status st, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_static_err, sizeof(g_static_err), fmt, ap);
+  va_end(ap);
+  return st;
+}
+
+__global__ void __launch_bounds__(256) k_static_zero(uint4* __restrict__ p, int64_t n16) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// hand the accumulated status bits to the caller's word and clear them for the next call
+__global__ void k_static_status(int32_t* __restrict__ dev_words, int32_t* __restrict__ d_status) {
+  *d_status = dev_words[0];
+  dev_words[0] = 0;
+}
+
+}  // namespace
+
+const char* emc2_static_last_error() { return g_static_err; }
+
+extern "C" emc2_status emc2_build_kmap_static(emc2_conv_kind kind, const int32_t* d_in_coords, const int32_t* d_n_in,
+                                              int64_t capacity_in, const int32_t grid_in[3], int32_t n_batch,
+                                              int64_t capacity_out, int32_t* d_out_coords, int32_t* d_n_out,
+                                              int32_t* d_nbr, int32_t grid_out[3], int32_t* d_status, void* stream) {
+  std::lock_guard<std::mutex> lock(g_static_mutex);   // host-side state only; device work is ordered by `stream`
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return static_fail(EMC2_ERR_DEVICE, "emc2_build_kmap_static: hipGetDevice: %s", hipGetErrorString(e));
+  if (device < 0 || device >= kStaticMaxDevices)
+    return static_fail(EMC2_ERR_UNSUPPORTED, "emc2_build_kmap_static: device %d outside [0, %d)", device, kStaticMaxDevices);
+  int64_t cells = 0;
+  if (!grid_in || !emc2_grid_ok(grid_in, n_batch, &cells))
+    return static_fail(EMC2_ERR_INVALID_ARG, "emc2_build_kmap_static: bad grid / batch");
+  if (cells > kStaticMaxCells)
+    return static_fail(EMC2_ERR_INVALID_ARG,
+                       "emc2_build_kmap_static: %lld cells exceed the static scratch's %lld (EMC2_STATIC_KMAP_MAX_CELLS); "
+                       "use emc2_build_kmap with a context",
+                       (long long)cells, (long long)kStaticMaxCells);
+  hipStream_t s = (hipStream_t)stream;
+  StaticKmap& sk = g_static[device];
+  if (!sk.ready) {
+    // this device's copy of the array: the symbol's name is not an address host code may pass to a kernel
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return static_fail(EMC2_ERR_DEVICE, "emc2_build_kmap_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+    sk.ptr = (unsigned char*)p;
+    memset(&sk.ctx, 0, sizeof(sk.ctx));
+    sk.ctx.device = device;
+    sk.ctx.max_points = 0;
+    sk.ctx.max_voxels = 1ll << 30;         // a kernel map needs no per-voxel scratch
+    sk.ctx.max_cells = kStaticMaxCells;
+    sk.ctx.n_slots = 0;                    // no caller-visible slots: both are the call's internal ones
+    sk.ctx.slot_tiles = kStaticTiles;
+    sk.ctx.slot_words = kStaticWords;
+    sk.slots[0] = (cellword_t*)sk.ptr;
+    sk.slots[1] = (cellword_t*)(sk.ptr + kStaticSlotPitch);
+    sk.ctx.slots = sk.slots;
+    sk.ctx.meta = sk.meta;
+    sk.ctx.partials = (uint32_t*)(sk.ptr + 2 * kStaticSlotPitch);
+    sk.ctx.n_partials = kStaticTiles + 1;
+    sk.ctx.dev_words = (int32_t*)(sk.ptr + 2 * kStaticSlotPitch + kStaticPartialsBytes);
+    // the tile-flag invariant (a tile without its flag holds no bit) and the status word start from zero; a fill
+    // kernel rather than a memset, so that a first call under stream capture records nothing unusual
+    const int64_t n16 = (int64_t)(kStaticBytes / 16);
+    hipLaunchKernelGGL(k_static_zero, dim3((unsigned)emc2_div_up(n16, 256)), dim3(256), 0, s, (uint4*)sk.ptr, n16);
+    e = hipGetLastError();
+    if (e != hipSuccess) return static_fail(EMC2_ERR_DEVICE, "emc2_build_kmap_static: zero fill: %s", hipGetErrorString(e));
+    sk.ready = true;
+  }
+  const emc2_status st = build_kmap_on(&sk.ctx, kind, d_in_coords, d_n_in, capacity_in, grid_in, n_batch, -1, -1, capacity_out,
+                                       d_out_coords, d_n_out, d_nbr, grid_out, nullptr, stream);
+  if (st != EMC2_OK) {
+    snprintf(g_static_err, sizeof(g_static_err), "%s", sk.ctx.err);
+    return st;
+  }
+  if (d_status) {
+    hipLaunchKernelGGL(k_static_status, dim3(1), dim3(1), 0, s, sk.ctx.dev_words, d_status);
+    e = hipGetLastError();
+    if (e != hipSuccess) return static_fail(EMC2_ERR_DEVICE, "emc2_build_kmap_static: status copy: %s", hipGetErrorString(e));
   }
   return EMC2_OK;
 }

@@ -40,4 +40,4 @@ def test_invalid_arguments_are_rejected_without_a_gpu_call():
     assert lib.emc2_create(ctypes.byref(h), 0, 0, 10, 10, 1) == binding.ERR_INVALID_ARG
     assert lib.emc2_create(ctypes.byref(h), 0, 10, 10, 10, 0) == binding.ERR_INVALID_ARG
     assert lib.emc2_status_sync(None, None) == binding.ERR_INVALID_ARG
-    assert lib.emc2_last_error(None) == b"null context"
+    assert lib.emc2_last_error(None) == b""             # no context: the text of the context-free call's last failure (none yet)
