@@ -11,6 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libemc2.so")
+PROBE_LIB = os.path.join(HERE, "libemc2probe.so")     # measurement probes of the bench (include/emc2_probe.h)
 SOURCES = ["context.hip", "cellindex.hip", "voxelize.hip", "kmap.hip", "spconv.hip", "spconv_mfma.hip", "spconv_span.hip",
            "spconv_direct.hip", "project.hip", "decoder.hip", "pool.hip", "dispatch.hip", "spconv_i8.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
@@ -39,11 +40,12 @@ def build(verbose: bool = False, force: bool = True, jobs: int = 8) -> str:
         return o
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        objs = list(ex.map(compile_one, SOURCES + ["probes.hip"]))
+    for lib, members in ((LIB, objs[:-1]), (PROBE_LIB, objs[-1:])):
+        cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + members
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return LIB
 
 

@@ -276,3 +276,101 @@ def make_context_for(cfg: Config, capacities: Optional[Dict[str, Sequence[int]]]
         max_vox = max(max_vox, max(caps))
         n_slots = max(n_slots, len(caps))
     return B.Context(n_points, max_vox, max_cells, n_slots=n_slots), n_points
+
+
+class ConfigRunner:
+    """Every branch of one workload configuration (config 3: three scales plus the point-to-image gather; config 5:
+    the near and the far expert), each on a context of its own so that the branches of one frame can share the GPU.
+    Only sequencing: one pass = every branch's voxelization, kernel maps and convolutions over the same points."""
+
+    def __init__(self, cfg: Config, n_points: int, capacities: Optional[Dict[str, Sequence[int]]] = None,
+                 device: str = "cuda"):
+        self.cfg = cfg
+        self.n_points = n_points
+        self.branches: List[Tuple[B.Context, BranchRunner]] = []
+        for br in cfg.branches:
+            caps = list(capacities[br.name]) if capacities and br.name in capacities else default_capacities(br, n_points)
+            ctx = B.Context(n_points, max(caps), cells_of(br.spec.grid, br.spec.n_batch), n_slots=len(caps))
+            seed = gen.frame_seed(cfg.index, 0) + len(br.name)
+            self.branches.append((ctx, BranchRunner(ctx, br, cfg.dtype, n_points, device_params(br.layers, seed, cfg.dtype),
+                                                    capacities=caps, device=device)))
+        self.side = [torch.cuda.Stream(device=device) for _ in self.branches[1:]]
+        self.camera = None
+        if cfg.camera is not None:
+            cam, seed = cfg.camera, gen.frame_seed(cfg.index, 0)
+            self.camera = {
+                "P": gen.make_camera(seed),
+                "img": torch.from_numpy(gen.make_image(cam.height, cam.width, cam.channels, seed)).to(device),
+                "out": torch.empty((n_points, cam.channels), dtype=torch.float16, device=device),
+                "valid": torch.empty((n_points,), dtype=torch.uint8, device=device),
+            }
+        self.graph = None
+
+    def close(self) -> None:
+        for ctx, _ in self.branches:
+            ctx.close()
+
+    def status_sync(self) -> None:
+        for ctx, _ in self.branches:
+            ctx.status_sync()
+
+    def _gather(self, points: torch.Tensor, tm) -> None:
+        if self.camera is not None:
+            c = self.camera
+            with tm("project_gather"):
+                self.branches[0][0].project_gather(points, c["P"], c["img"], c["out"], c["valid"])
+
+    def run(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> List[torch.Tensor]:
+        """Everything on the current stream, one call after the other."""
+        tm = timer if timer is not None else _no_timer
+        outs = []
+        for bi, (_, r) in enumerate(self.branches):
+            outs.append(r.run(points, batch, (lambda tag, bi=bi: tm((bi, tag))) if timer is not None else None))
+        self._gather(points, tm)
+        return outs
+
+    def run_overlapped(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> List[torch.Tensor]:
+        """Branches side by side: the first on the current stream, the others on streams of their own that fork
+        from it and join it again; inside a branch, map building overlaps the convolutions as in BranchRunner."""
+        tm = timer if timer is not None else _no_timer
+        main = torch.cuda.current_stream()
+        outs: List[Optional[torch.Tensor]] = [None] * len(self.branches)
+        for bi, (_, r) in enumerate(self.branches[1:], start=1):
+            s = self.side[bi - 1]
+            s.wait_stream(main)
+            with torch.cuda.stream(s):
+                outs[bi] = r.run_overlapped(points, batch, (lambda tag, bi=bi: tm((bi, tag))) if timer is not None else None,
+                                            _capturing=True)
+        outs[0] = self.branches[0][1].run_overlapped(points, batch, (lambda tag: tm((0, tag))) if timer is not None else None,
+                                                     _capturing=True)
+        self._gather(points, tm)
+        for s in self.side:
+            main.wait_stream(s)
+        return outs
+
+    def capture(self, points: torch.Tensor, batch: Optional[torch.Tensor], overlapped: bool = True) -> None:
+        """Record one HIP graph per branch (BranchRunner.capture: the branch's two streams with their events, no
+        memset nodes); replay() then launches them side by side.  One graph per branch, not one for the whole
+        configuration: a capture in which a forked stream forks again (branch stream -> its map stream) ended in a
+        crash inside the runtime's end-of-capture on this ROCm, whereas a single level of forking is what the
+        per-branch graphs have always used."""
+        for _, r in self.branches:
+            r.capture(points, batch, overlapped=overlapped)
+        self.graph_points = points
+        self.graph_out = [r.graph_out for _, r in self.branches]
+        self.graph = True
+
+    def replay(self) -> List[torch.Tensor]:
+        """Replay the captured graphs: the first branch on the current stream, the others on streams of their own
+        that fork from it and join it again (ordinary stream and event calls, outside any capture)."""
+        main = torch.cuda.current_stream()
+        for bi, (_, r) in enumerate(self.branches[1:], start=1):
+            s = self.side[bi - 1]
+            s.wait_stream(main)
+            with torch.cuda.stream(s):
+                r.graph.replay()
+        self.branches[0][1].graph.replay()
+        self._gather(self.graph_points, _no_timer)
+        for s in self.side:
+            main.wait_stream(s)
+        return self.graph_out
