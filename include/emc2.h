@@ -102,7 +102,10 @@ typedef enum { EMC2_F32 = 0, EMC2_F16 = 1, EMC2_BF16 = 2, EMC2_I8 = 3 } emc2_dty
  * d_batch: [n_points] int32 or NULL (all points in frame 0).
  * index_slot in [0, n_slots): the cell index of the produced voxel set is left in that slot for
  * emc2_build_kmap to reuse; it stays valid until another call writes the same slot.
- * Means are accumulated with fp32 atomics (order not fixed; result within a few ulp of exact).
+ * A voxel of up to four points is summed in fp32 in the order of the points' values, so its mean is the same bit for
+ * bit in every run and for every order of the input; the points beyond the fourth are added with fp32 atomics
+ * (order not fixed; result within a few ulp of exact).  Rows [n_voxels, min(n_points, capacity)) of d_feats and
+ * d_counts are zeroed.
  */
 emc2_status emc2_voxelize(emc2_ctx* ctx, const float* d_points, const int32_t* d_batch,
                           int64_t n_points, const emc2_voxel_spec* spec, int64_t capacity,

@@ -5,22 +5,25 @@
 
 namespace {
 
-// One block per tile: a flagged tile is zeroed (16 KB) and its flag lowered; the others cost one load.
-__global__ void __launch_bounds__(256) k_index_clear(uint4* __restrict__ p, uint32_t* __restrict__ flags) {
-  const uint32_t f = flags[blockIdx.x];
-  if (!f) return;  // uniform for the block
-  uint4* t = p + (int64_t)blockIdx.x * (EMC2_SCAN_TILE / 2);
+// One block per tile; thread t owns the half line (8 words, 64 bytes) t of the tile.  Flagged lines are zeroed and
+// their flags lowered; a tile without a flagged line costs one 128-byte read.
+__global__ void __launch_bounds__(256) k_index_clear(uint4* __restrict__ p, lineflag_t* __restrict__ flags) {
+  lineflag_t* tf = flags + (int64_t)blockIdx.x * EMC2_LINES_PER_TILE;
+  const lineflag_t f = tf[threadIdx.x >> 1];
+  if (f) {
+    uint4* t = p + ((int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8) / 2;
 #pragma unroll
-  for (int i = 0; i < EMC2_SCAN_TILE / 2 / 256; ++i) t[i * 256 + threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
-  __syncthreads();  // every thread has read the flag
-  if (threadIdx.x == 0) flags[blockIdx.x] = 0u;
+    for (int i = 0; i < 4; ++i) t[i] = make_uint4(0u, 0u, 0u, 0u);
+  }
+  if (!__syncthreads_or(f != 0)) return;  // every thread has read its flag
+  if (f && !(threadIdx.x & 1)) tf[threadIdx.x >> 1] = 0;
 }
 
 __global__ void __launch_bounds__(256) k_index_mark_coords(cellword_t* __restrict__ idx,
                                                            const int4* __restrict__ coords,
                                                            const int32_t* __restrict__ d_n, int64_t capacity,
                                                            int gx, int gy, int gz, int n_batch,
-                                                           uint32_t* __restrict__ flags) {
+                                                           lineflag_t* __restrict__ flags) {
   int64_t n = *d_n;
   if (n > capacity) n = capacity;
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -31,7 +34,7 @@ __global__ void __launch_bounds__(256) k_index_mark_coords(cellword_t* __restric
     return;  // malformed coordinate: ignore rather than write out of bounds
   const uint64_t key = (((uint64_t)c.x * gz + (uint64_t)c.y) * gy + (uint64_t)c.z) * gx + (uint64_t)c.w;
   atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
-  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
+  flags[emc2_line_of_key(key)] = 1;
 }
 
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
@@ -46,16 +49,19 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
 // Per-block popcount totals.  Thread t owns the 8 consecutive words [8t, 8t+8) of its tile.
 __global__ void __launch_bounds__(256) k_scan_reduce(const cellword_t* __restrict__ idx, int64_t n_words,
                                                      uint32_t* __restrict__ partials,
-                                                     const uint32_t* __restrict__ flags) {
-  if (!flags[blockIdx.x]) {  // no bit in this tile (uniform for the block)
+                                                     const lineflag_t* __restrict__ flags) {
+  const bool mine = flags[(int64_t)blockIdx.x * EMC2_LINES_PER_TILE + (threadIdx.x >> 1)] != 0;
+  if (!__syncthreads_or(mine)) {  // no bit in this tile
     if (threadIdx.x == 0) partials[blockIdx.x] = 0u;
     return;
   }
   const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
   uint32_t s = 0;
+  if (mine) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
-    if (base + j < n_words) s += __popc(idx[base + j].x);
+    for (int j = 0; j < 8; ++j)
+      if (base + j < n_words) s += __popc(idx[base + j].x);
+  }
   __shared__ uint32_t wsum[4];
   const uint32_t inc = wave_inclusive_scan(s);
   if ((threadIdx.x & 63) == 63) wsum[threadIdx.x >> 6] = inc;
@@ -99,14 +105,15 @@ __global__ void __launch_bounds__(1024) k_scan_partials(uint32_t* __restrict__ p
 // Write each word's exclusive prefix (.y).
 __global__ void __launch_bounds__(256) k_scan_apply(cellword_t* __restrict__ idx, int64_t n_words,
                                                     const uint32_t* __restrict__ partials,
-                                                    const uint32_t* __restrict__ flags) {
-  if (!flags[blockIdx.x]) return;  // no bit, so no prefix field anybody reads
+                                                    const lineflag_t* __restrict__ flags) {
+  const bool mine = flags[(int64_t)blockIdx.x * EMC2_LINES_PER_TILE + (threadIdx.x >> 1)] != 0;
+  if (!__syncthreads_or(mine)) return;  // no bit, so no prefix field anybody reads
   const int64_t base = (int64_t)blockIdx.x * EMC2_SCAN_TILE + (int64_t)threadIdx.x * 8;
   uint32_t bits[8];
   uint32_t s = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    bits[j] = (base + j < n_words) ? idx[base + j].x : 0u;
+    bits[j] = (mine && base + j < n_words) ? idx[base + j].x : 0u;
     s += __popc(bits[j]);
   }
   __shared__ uint32_t wsum[4];
@@ -116,10 +123,12 @@ __global__ void __launch_bounds__(256) k_scan_apply(cellword_t* __restrict__ idx
   uint32_t run = partials[blockIdx.x] + inc - s;
   const int w = threadIdx.x >> 6;
   for (int j = 0; j < w; ++j) run += wsum[j];
+  if (mine) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
-    run += __popc(bits[j]);
+    for (int j = 0; j < 8; ++j) {
+      if (base + j < n_words) idx[base + j] = make_uint2(bits[j], run);
+      run += __popc(bits[j]);
+    }
   }
 }
 
@@ -155,14 +164,14 @@ __global__ void __launch_bounds__(1024) k_scan_small(cellword_t* __restrict__ id
 }
 
 // Apply step that derives its own base from the block totals (no separate scan of the totals): block b
-// sums totals[0..b) cooperatively.  Quadratic in the number of blocks, so only used while that is small.
+// sums totals[0..b) cooperatively.  Quadratic in the number of blocks, so only used while that is moderate.
 __global__ void __launch_bounds__(256) k_scan_apply_self(cellword_t* __restrict__ idx, int64_t n_words,
                                                          const uint32_t* __restrict__ totals, int64_t capacity,
                                                          int32_t* __restrict__ d_total, int32_t* __restrict__ d_flags,
-                                                         const uint32_t* __restrict__ flags) {
-  // a tile without bits has no prefix field anybody reads; the last block still reports the total
-  const bool has_bits = flags[blockIdx.x] != 0u;
-  if (!has_bits && blockIdx.x != gridDim.x - 1) return;  // uniform for the block
+                                                         const lineflag_t* __restrict__ flags) {
+  // a line without bits has no prefix field anybody reads; the last block still reports the total
+  const bool has_bits = flags[(int64_t)blockIdx.x * EMC2_LINES_PER_TILE + (threadIdx.x >> 1)] != 0;   // this thread's line
+  if (!__syncthreads_or(has_bits) && blockIdx.x != gridDim.x - 1) return;
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t base_s;
   uint32_t part = 0;
@@ -229,7 +238,7 @@ void emc2_index_scan(emc2_ctx* ctx, cellword_t* idx, int64_t n_cells, int64_t ca
   }
   hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
                      emc2_slot_flags(ctx, idx));
-  if (n_blocks <= 2048) {
+  if (n_blocks <= 16384) {   // each apply block re-sums the earlier totals itself: at most 64 KB from L2
     hipLaunchKernelGGL(k_scan_apply_self, dim3((unsigned)n_blocks), dim3(256), 0, stream, idx, n_words, ctx->partials,
                        capacity, d_total, ctx->dev_words, emc2_slot_flags(ctx, idx));
     return;

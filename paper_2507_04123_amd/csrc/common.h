@@ -70,7 +70,7 @@ struct emc2_ctx {
   int device;
   int64_t max_points, max_voxels, max_cells;
   int32_t n_slots;          // user-visible slots; two more internal ones follow
-  int64_t slot_words;       // cellwords per slot (a whole number of tiles); the tile flags follow them
+  int64_t slot_words;       // cellwords per slot (a whole number of tiles); the line flags follow them
   int64_t slot_tiles;
   cellword_t** slots;       // host array [n_slots + 2] of device pointers
   SlotMeta* meta;           // host array [n_slots + 2]
@@ -93,15 +93,22 @@ struct emc2_ctx {
 
 #define EMC2_SCAN_TILE 2048  // cellwords per scan block (256 threads x 8)
 #define EMC2_TILE_SHIFT 11   // log2(EMC2_SCAN_TILE)
+#define EMC2_LINE_SHIFT 4    // log2 of the cellwords per flagged line: 16 words = 128 bytes = 512 cells
+#define EMC2_LINES_PER_TILE (EMC2_SCAN_TILE >> EMC2_LINE_SHIFT)
 
-// Tile flags of an index slot.  The active cells of a LiDAR frame fill a fraction of a percent of the
-// finest grid, so every index slot carries one flag per 2048-word tile, stored behind its words:
-// INVARIANT: a tile whose flag is 0 holds no occupancy bit (its prefix fields are unspecified and never
-// read: a lookup tests the bit first).  Every kernel that sets bits raises the flag of the tile it writes;
-// clear, scan and the stride-2 marking skip unflagged tiles instead of streaming the whole grid.
-static inline uint32_t* emc2_slot_flags(const emc2_ctx* ctx, cellword_t* idx) {
-  return reinterpret_cast<uint32_t*>(idx + ctx->slot_words);
+// Line flags of an index slot.  The active cells of a LiDAR frame fill a fraction of a percent of the finest
+// grid, and scattered objects touch single cache lines of it, so every index slot carries one flag byte per
+// 128-byte line (16 words, 512 cells), stored behind its words:
+// INVARIANT: a line whose flag is 0 holds no occupancy bit (its prefix fields are unspecified and never
+// read: a lookup tests the bit first).  Every kernel that sets bits raises the flag of the line it writes
+// (a plain byte store: all writers store the same value); clear, scan, the stride-2 marking and the
+// expansion to coordinates read a tile's 128 flag bytes first and touch only the flagged lines.
+typedef uint8_t lineflag_t;
+static inline lineflag_t* emc2_slot_flags(const emc2_ctx* ctx, cellword_t* idx) {
+  return reinterpret_cast<lineflag_t*>(idx + ctx->slot_words);
 }
+// flag index of the line that holds cell `key`
+__host__ __device__ __forceinline__ uint64_t emc2_line_of_key(uint64_t key) { return key >> (5 + EMC2_LINE_SHIFT); }
 
 // host helpers (context.hip)
 emc2_status emc2_fail(emc2_ctx* ctx, emc2_status st, const char* fmt, ...);

@@ -61,9 +61,9 @@ extern "C" emc2_status emc2_create(emc2_ctx** out, int device, int64_t max_point
   ctx->meta = (SlotMeta*)calloc((size_t)n_slots + 2, sizeof(SlotMeta));
   if (!ctx->slots || !ctx->meta) { st = EMC2_ERR_DEVICE; goto fail; }
   for (int s = 0; s < n_slots + 2; ++s) {
-    const size_t bytes = sizeof(cellword_t) * (size_t)ctx->slot_words + sizeof(uint32_t) * (size_t)ctx->slot_tiles;
+    const size_t bytes = sizeof(cellword_t) * (size_t)ctx->slot_words + sizeof(lineflag_t) * (size_t)(ctx->slot_words >> EMC2_LINE_SHIFT);
     TRY(hipMalloc((void**)&ctx->slots[s], bytes), "hipMalloc(index slot)");
-    TRY(hipMemset(ctx->slots[s], 0, bytes), "hipMemset(index slot)");  // establishes the tile-flag invariant
+    TRY(hipMemset(ctx->slots[s], 0, bytes), "hipMemset(index slot)");  // establishes the line-flag invariant
   }
   TRY(hipMalloc((void**)&ctx->stash, sizeof(float4) * EMC2_VOX_STASH * (size_t)max_voxels), "hipMalloc(voxel stash)");
   ctx->n_partials = emc2_div_up(ctx->slot_words, EMC2_SCAN_TILE) + 1;

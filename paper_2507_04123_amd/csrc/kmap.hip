@@ -35,11 +35,11 @@ __device__ __forceinline__ uint32_t compress_even_bits(uint64_t v) {
 __global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restrict__ in_idx, int64_t n_in_words,
                                                       int64_t n_in_cells, cellword_t* __restrict__ out_idx, int gx, int gy,
                                                       int gz, int gox, int goy, int goz,
-                                                      const uint32_t* __restrict__ in_flags,
-                                                      uint32_t* __restrict__ out_flags) {
+                                                      const lineflag_t* __restrict__ in_flags,
+                                                      lineflag_t* __restrict__ out_flags) {
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_in_words) return;
-  if (!in_flags[w >> EMC2_TILE_SHIFT]) return;   // no bit in this tile of the input (uniform for the wave)
+  if (!in_flags[w >> EMC2_LINE_SHIFT]) return;   // no bit in this line of the input (uniform for 16 lanes)
   uint32_t bits = in_idx[w].x;
   while (bits) {
     // row segment of the word that starts at the first set bit's row
@@ -70,10 +70,10 @@ __global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restri
         const uint64_t okey = ((b * goz + (uint64_t)(z0 + dz)) * goy + (uint64_t)(y0 + dy)) * gox + (uint64_t)ob;
         const uint32_t sh = (uint32_t)okey & 31u;
         atomicOr(&out_idx[okey >> 5].x, m << sh);
-        out_flags[okey >> (5 + EMC2_TILE_SHIFT)] = 1u;
+        out_flags[emc2_line_of_key(okey)] = 1;
         if (sh != 0 && (m >> (32u - sh)) != 0) {
           atomicOr(&out_idx[(okey >> 5) + 1].x, m >> (32u - sh));
-          out_flags[((okey >> 5) + 1) >> EMC2_TILE_SHIFT] = 1u;
+          out_flags[((okey >> 5) + 1) >> EMC2_LINE_SHIFT] = 1;
         }
       }
   }
@@ -82,9 +82,11 @@ __global__ void __launch_bounds__(256) k_strided_mark(const cellword_t* __restri
 // One thread per cellword: expand set bits into coordinates at their rank.  The word's first cell is decoded
 // once; later bits advance x with carries (a word rarely crosses a row end), so no division per bit.
 __global__ void __launch_bounds__(256) k_expand_coords(const cellword_t* __restrict__ idx, int64_t n_words, int64_t capacity,
-                                                       int gx, int gy, int gz, int4* __restrict__ coords) {
+                                                       int gx, int gy, int gz, const lineflag_t* __restrict__ flags,
+                                                       int4* __restrict__ coords) {
   const int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (w >= n_words) return;
+  if (!flags[w >> EMC2_LINE_SHIFT]) return;     // no bit in this line (uniform for 16 lanes)
   const cellword_t cw = idx[w];
   uint32_t bits = cw.x;
   if (!bits) return;
@@ -259,7 +261,7 @@ emc2_status build_kmap_on(emc2_ctx* ctx, emc2_conv_kind kind, const int32_t* d_i
     emc2_index_scan(ctx, out_idx, cells_out, capacity_out, d_n_out, s);
     const int64_t n_words = emc2_div_up(cells_out, 32);
     hipLaunchKernelGGL(k_expand_coords, dim3((unsigned)emc2_div_up(n_words, 256)), dim3(256), 0, s, out_idx, n_words,
-                       capacity_out, go[0], go[1], go[2], (int4*)d_out_coords);
+                       capacity_out, go[0], go[1], go[2], emc2_slot_flags(ctx, out_idx), (int4*)d_out_coords);
     out_coords = d_out_coords;
     hipLaunchKernelGGL(k_probe<2>, dim3((unsigned)emc2_div_up(capacity_out, 256)), dim3(256), 0, s, (const int4*)out_coords,
                        d_n_out, capacity_out, in_idx, d_n_in, grid_in[0], grid_in[1], grid_in[2], n_batch, d_nbr);
@@ -291,7 +293,7 @@ extern "C" emc2_status emc2_build_kmap(emc2_ctx* ctx, emc2_conv_kind kind, const
 
 // ---------------------------------------------------------------------------------------------------------
 // emc2_build_kmap_static: the same call for callers that must not allocate.  Everything emc2_build_kmap keeps in
-// a context's scratch (two cell-index slots with their tile flags, the scan's partial sums, the status and
+// a context's scratch (two cell-index slots with their line flags, the scan's partial sums, the status and
 // count words) lives in one file-scope device array instead; each GPU holds its own copy at its own address,
 // looked up once per device, and a host-side context structure per device points into it.
 // ---------------------------------------------------------------------------------------------------------
@@ -300,7 +302,7 @@ namespace {
 constexpr int64_t kStaticMaxCells = EMC2_STATIC_KMAP_MAX_CELLS;
 constexpr int64_t kStaticTiles = (kStaticMaxCells / 32 + 1 + EMC2_SCAN_TILE - 1) / EMC2_SCAN_TILE;   // as emc2_create sizes a slot
 constexpr int64_t kStaticWords = kStaticTiles * EMC2_SCAN_TILE;
-constexpr size_t kStaticSlotBytes = sizeof(cellword_t) * (size_t)kStaticWords + sizeof(uint32_t) * (size_t)kStaticTiles;
+constexpr size_t kStaticSlotBytes = sizeof(cellword_t) * (size_t)kStaticWords + sizeof(lineflag_t) * (size_t)(kStaticWords >> EMC2_LINE_SHIFT);
 constexpr size_t kStaticSlotPitch = (kStaticSlotBytes + 255) / 256 * 256;
 constexpr size_t kStaticPartialsBytes = ((size_t)(kStaticTiles + 1) * sizeof(uint32_t) + 255) / 256 * 256;
 constexpr size_t kStaticBytes = 2 * kStaticSlotPitch + kStaticPartialsBytes + 256;   // + status / count words
@@ -384,7 +386,7 @@ extern "C" emc2_status emc2_build_kmap_static(emc2_conv_kind kind, const int32_t
     sk.ctx.partials = (uint32_t*)(sk.ptr + 2 * kStaticSlotPitch);
     sk.ctx.n_partials = kStaticTiles + 1;
     sk.ctx.dev_words = (int32_t*)(sk.ptr + 2 * kStaticSlotPitch + kStaticPartialsBytes);
-    // the tile-flag invariant (a tile without its flag holds no bit) and the status word start from zero; a fill
+    // the line-flag invariant (a line without its flag holds no bit) and the status word start from zero; a fill
     // kernel rather than a memset, so that a first call under stream capture records nothing unusual
     const int64_t n16 = (int64_t)(kStaticBytes / 16);
     hipLaunchKernelGGL(k_static_zero, dim3((unsigned)emc2_div_up(n16, 256)), dim3(256), 0, s, (uint4*)sk.ptr, n16);

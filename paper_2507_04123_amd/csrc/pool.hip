@@ -82,7 +82,7 @@ __device__ __forceinline__ PixCell lift(const float* __restrict__ depth, int64_t
 // a stale read can only cost a redundant atomic).  The same launch zeroes what later passes accumulate into:
 // the per-cell counters (at most min(pixels, capacity) cells exist) and the boundary accumulators.
 __global__ void __launch_bounds__(256) k_pool_mark(const float* __restrict__ depth, int64_t npix, PoolParams prm,
-                                                   cellword_t* __restrict__ idx, uint32_t* __restrict__ flags,
+                                                   cellword_t* __restrict__ idx, lineflag_t* __restrict__ flags,
                                                    int32_t* __restrict__ counts, int64_t n_counts, uint4* __restrict__ acc16,
                                                    int64_t n_acc16) {
   const int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -96,7 +96,7 @@ __global__ void __launch_bounds__(256) k_pool_mark(const float* __restrict__ dep
   const uint32_t bit = 1u << ((uint32_t)key & 31u);
   if (idx[key >> 5].x & bit) return;
   atomicOr(&idx[key >> 5].x, bit);
-  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
+  flags[emc2_line_of_key(key)] = 1;
 }
 
 // Position of every pixel within its cell.  A run of consecutive lanes with the same rank takes its positions from
@@ -441,7 +441,7 @@ __device__ __forceinline__ bool fuse_key(const int4 c, int gx, int gy, int gz, i
 __global__ void __launch_bounds__(256) k_fuse_mark(const int4* __restrict__ coords_l, const int32_t* __restrict__ d_n_l,
                                                    int64_t capacity_l, const int4* __restrict__ coords_i,
                                                    const int32_t* __restrict__ d_n_i, int64_t capacity_i,
-                                                   cellword_t* __restrict__ idx, uint32_t* __restrict__ flags, int gx, int gy,
+                                                   cellword_t* __restrict__ idx, lineflag_t* __restrict__ flags, int gx, int gy,
                                                    int gz, int n_batch, int64_t bound, int32_t* __restrict__ src_l,
                                                    int32_t* __restrict__ src_i) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -458,7 +458,7 @@ __global__ void __launch_bounds__(256) k_fuse_mark(const int4* __restrict__ coor
   uint64_t key;
   if (!fuse_key((is_l ? coords_l : coords_i)[i], gx, gy, gz, n_batch, &key)) return;
   atomicOr(&idx[key >> 5].x, 1u << ((uint32_t)key & 31u));
-  flags[key >> (5 + EMC2_TILE_SHIFT)] = 1u;
+  flags[emc2_line_of_key(key)] = 1;
 }
 
 // One thread per input row of either set: its rank in the union index is its output row.

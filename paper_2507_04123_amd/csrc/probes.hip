@@ -11,9 +11,15 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 __global__ void k_probe_empty() {}
 
+// four independent 16-byte loads in flight per thread before the first store
 __global__ void __launch_bounds__(256) k_probe_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, int64_t n16) {
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    dst[i] = a; dst[i + stride] = b; dst[i + 2 * stride] = c; dst[i + 3 * stride] = d;
+  }
+  for (; i < n16; i += stride) dst[i] = src[i];
 }
 
 __global__ void __launch_bounds__(256) k_probe_mfma_f16(int64_t iters, float* __restrict__ sink) {
@@ -53,7 +59,7 @@ extern "C" int32_t emc2_probe_copy(void* dst, const void* src, int64_t bytes, vo
   if (bytes == 0) return 0;
   const int64_t n16 = bytes / 16;
   int64_t blocks = (n16 + 255) / 256;
-  if (blocks > 256 * 32) blocks = 256 * 32;   // 32 blocks per CU, the rest by grid stride
+  if (blocks > 256 * 16) blocks = 256 * 16;   // 16 blocks per CU, the rest by grid stride
   hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, (const uint4*)src, n16);
   return (int32_t)hipGetLastError();
 }

@@ -2,13 +2,14 @@
 // Sec. 3.5 configurable pool size; Sec. 3.6 (3) prefix-sum index search).
 //
 // The voxel index of a cell is its rank in the prefix-summed cell index, so no hash table is needed:
-// Pass 1 (one thread per point): cell key -> set the cell's bit in the index (one atomic OR per point).
+// Pass 1 (one thread per point): cell key -> set the cell's bit in the index (one atomic OR per point); the same
+//   launch zeroes the output rows pass 2 accumulates into.
 // Scan: prefix sum over the index -> the rank of every active cell = its position in key order, and the
 //   number of voxels.
 // Pass 2 (one thread per point): the same key again -> rank r (one 8-byte load) -> position within the
 //   voxel from one returning atomic add on counts[r] -> the point goes to slot `pos` of the voxel's stash
 //   (a plain 16-byte store); only points beyond the stash depth are added atomically into the output row.
-// Pass 3 (one thread per voxel): sum the stash, divide, write the means.
+// Pass 3 (one thread per voxel): sum the stash in the order of the points' values, divide, write the means.
 // Device-scope atomics on this part execute at the memory side of the fabric (the L2s of the 8 XCDs are
 // not coherent with each other), about 17 G/s in aggregate: two per point instead of seven is what
 // this layout buys.
@@ -78,22 +79,18 @@ __device__ __forceinline__ PointCell locate(const float* __restrict__ points, co
 
 __global__ void __launch_bounds__(256) k_vox_mark(const float* __restrict__ points, const int32_t* __restrict__ batch,
                                                   int64_t n_points, VoxParams prm, cellword_t* __restrict__ idx,
-                                                  uint32_t* __restrict__ flags) {
-  const PointCell pc = locate(points, batch, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, n_points, prm);
+                                                  lineflag_t* __restrict__ flags, int64_t zero_rows,
+                                                  float4* __restrict__ feats, int32_t* __restrict__ counts) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  // the rows pass 2 accumulates into: there are at most min(n_points, capacity) voxels, one thread each
+  if (i < zero_rows) {
+    feats[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    counts[i] = 0;
+  }
+  const PointCell pc = locate(points, batch, i, n_points, prm);
   if (!pc.keep) return;
   atomicOr(&idx[pc.key >> 5].x, 1u << ((uint32_t)pc.key & 31u));
-  flags[pc.key >> (5 + EMC2_TILE_SHIFT)] = 1u;   // this tile of the index now holds a bit
-}
-
-// Rows [0, n_voxels) of the outputs that pass 2 accumulates into.
-__global__ void __launch_bounds__(256) k_vox_zero(const int32_t* __restrict__ d_n, int64_t capacity,
-                                                  float4* __restrict__ feats, int32_t* __restrict__ counts) {
-  int64_t n = *d_n;
-  if (n > capacity) n = capacity;
-  const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (r >= n) return;
-  feats[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-  counts[r] = 0;
+  flags[emc2_line_of_key(pc.key)] = 1;   // this line of the index now holds a bit
 }
 
 __global__ void __launch_bounds__(256) k_vox_scatter(const float* __restrict__ points, const int32_t* __restrict__ batch,
@@ -129,10 +126,27 @@ __global__ void __launch_bounds__(256) k_vox_finalize(const int32_t* __restrict_
   const int32_t cnt = counts[r];
   float4 s = feats[r];   // what overflowed the stash (zero for almost every voxel)
   const int k = cnt < EMC2_VOX_STASH ? cnt : EMC2_VOX_STASH;
-  for (int j = 0; j < k; ++j) {
-    const float4 v = stash[r * EMC2_VOX_STASH + j];
-    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
-  }
+  // The stash holds the points in arrival order, which differs from run to run.  They are summed in the order
+  // of their values (x, then y, z, intensity) instead, so that a voxel of up to EMC2_VOX_STASH points -- nearly
+  // every voxel of a LiDAR frame -- gets the same mean, bit for bit, in every run and for every order of the input.
+  float4 v[EMC2_VOX_STASH];
+#pragma unroll
+  for (int j = 0; j < EMC2_VOX_STASH; ++j)
+    v[j] = j < k ? stash[r * EMC2_VOX_STASH + j] : make_float4(INFINITY, INFINITY, INFINITY, INFINITY);
+  auto before = [](const float4& a, const float4& b) {
+    if (a.x != b.x) return a.x < b.x;
+    if (a.y != b.y) return a.y < b.y;
+    if (a.z != b.z) return a.z < b.z;
+    return a.w < b.w;
+  };
+  auto order = [&](int a, int b) {   // compare-exchange: v[a] <= v[b] afterwards
+    if (before(v[b], v[a])) { const float4 t = v[a]; v[a] = v[b]; v[b] = t; }
+  };
+  static_assert(EMC2_VOX_STASH == 4, "the sorting network below orders four entries");
+  order(0, 1); order(2, 3); order(0, 2); order(1, 3); order(1, 2);
+#pragma unroll
+  for (int j = 0; j < EMC2_VOX_STASH; ++j)
+    if (j < k) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
   const float c = (float)cnt;
   const float4 m = make_float4(s.x / c, s.y / c, s.z / c, s.w / c);
   feats[r] = m;
@@ -195,15 +209,15 @@ extern "C" emc2_status emc2_voxelize(emc2_ctx* ctx, const float* d_points, const
 
   emc2_index_clear(ctx, idx, s);
   const dim3 pg((unsigned)emc2_div_up(n_points > 0 ? n_points : 1, 256)), blk(256);
+  // at most min(n_points, capacity) voxels exist
+  const int64_t bound = n_points < capacity ? n_points : capacity;
   if (n_points > 0)
-    hipLaunchKernelGGL(k_vox_mark, pg, blk, 0, s, d_points, d_batch, n_points, prm, idx, emc2_slot_flags(ctx, idx));
+    hipLaunchKernelGGL(k_vox_mark, pg, blk, 0, s, d_points, d_batch, n_points, prm, idx, emc2_slot_flags(ctx, idx), bound,
+                       (float4*)d_feats, d_counts);
   emc2_index_scan(ctx, idx, n_cells, capacity, d_n_voxels, s);
   {
-    // at most min(n_points, capacity) voxels exist
-    const int64_t bound = n_points < capacity ? n_points : capacity;
     if (bound > 0) {
       const dim3 vg((unsigned)emc2_div_up(bound, 256));
-      hipLaunchKernelGGL(k_vox_zero, vg, blk, 0, s, d_n_voxels, capacity, (float4*)d_feats, d_counts);
       hipLaunchKernelGGL(k_vox_scatter, pg, blk, 0, s, d_points, d_batch, n_points, prm, idx, capacity, (int4*)d_coords,
                          (float4*)d_feats, d_counts, ctx->stash);
       const int lp = d_feats_lp ? (lp_dtype == EMC2_F16 ? 1 : 2) : 0;
