@@ -214,7 +214,7 @@ emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, 
 #define EMC2_MAP_ANY (-1)
 /*
  * Name of the device kernel emc2_spconv launches for these arguments ("k_spconv_span", "k_spconv_direct",
- * "k_spconv_mfma", "k_spconv_small" or "k_spconv_alu"): lets a profile be matched to a layer.  Host-only
+ * "k_spconv_mfma", "k_spconv_rows", "k_spconv_small" or "k_spconv_alu"): lets a profile be matched to a layer.  Host-only
  * query about this library's kernel selection (no GPU work, no passage of the paper behind it); the string
  * is static.  NULL for a dtype emc2_spconv rejects.
  */

@@ -142,6 +142,176 @@ __global__ void __launch_bounds__(256) k_spconv_small(const T* __restrict__ in, 
   for (int q = 0; q < OUT_BYTES / 16; ++q) reinterpret_cast<u32x4_t*>(dst)[q] = reinterpret_cast<const u32x4_t*>(yr)[q];
 }
 
+// Small-channel 16-bit kernel on the matrix cores (Cin in {4, 16}, Cout in {16, 32}).  Memory access as in
+// k_spconv_small -- lane = output row, every kernel-map entry and feature row requested with whole-wave loads that
+// touch a few cache lines each -- but the contraction runs on v_mfma_f32_4x4x4 (16 blocks of 4x4x4 per instruction):
+// as the B operand, lane l supplies 4 input channels of ITS row (8 bytes, exactly what it loaded); as the A
+// operand it supplies W[tap][4 channels][4g + l % 4], the same 4x4 weight block for every block of rows; the result
+// leaves 4 consecutive output channels of row l in lane l's four accumulator registers, so the epilogue is
+// per-lane and the stores are whole 16-byte pieces of the lane's own row.  The vector-ALU kernel spends its time
+// re-reading weights from LDS for every multiply-add (one LDS read per 4 of them); here a weight block is read
+// once per tap and 4 channels for two groups of 64 rows, and a tap none of the 128 rows has costs nothing.
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+template <int DT> struct Mma4;
+template <> struct Mma4<EMC2_F16> {
+  static __device__ __forceinline__ float4_t run(u32x2_t a, u32x2_t b, float4_t c) {
+    return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, a), __builtin_bit_cast(half4_t, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t cvt2(float lo, float hi) {
+    return (uint32_t)__half_as_ushort(__float2half_rn(lo)) | ((uint32_t)__half_as_ushort(__float2half_rn(hi)) << 16);
+  }
+};
+template <> struct Mma4<EMC2_BF16> {
+  static __device__ __forceinline__ float4_t run(u32x2_t a, u32x2_t b, float4_t c) {
+    return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(__builtin_bit_cast(short4_t, a), __builtin_bit_cast(short4_t, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ uint32_t cvt2(float lo, float hi) {
+    return (uint32_t)__builtin_bit_cast(uint16_t, __float2bfloat16(lo)) |
+           ((uint32_t)__builtin_bit_cast(uint16_t, __float2bfloat16(hi)) << 16);
+  }
+};
+
+template <int DT, int CIN, int COUT>
+__global__ void __launch_bounds__(256) k_spconv_rows(const uint16_t* __restrict__ in, const uint16_t* __restrict__ w,
+                                                     const float* __restrict__ scale, const float* __restrict__ shift,
+                                                     int epilogue, const int32_t* __restrict__ nbr,
+                                                     const int32_t* __restrict__ d_n_out, int64_t capacity_out,
+                                                     int32_t n_in, int32_t* __restrict__ dev_flags,
+                                                     uint16_t* __restrict__ out) {
+  constexpr int KB = CIN / 4;                 // 4-channel blocks of an input row
+  constexpr int G = COUT / 4;                 // 4-channel groups of an output row
+  constexpr int RG = 2;                       // groups of 64 rows per wave (a weight block read serves both)
+  constexpr int TB = CIN == 4 ? 9 : 3;        // taps whose rows are in flight together
+  constexpr int RW = CIN / 2;                 // 32-bit words per input row
+  static_assert(27 % TB == 0 && CIN % 4 == 0 && COUT % 8 == 0, "shapes this kernel covers");
+  // weights as A operands: wl[((tap * KB + kb) * G + g) * 4 + j] = W[tap][4kb + 0..3][4g + j], 8 bytes
+  __shared__ u32x2_t wl[27 * KB * G * 4];
+  for (int e = threadIdx.x; e < 27 * KB * G * 4; e += 256) {
+    const int j = e & 3;
+    int f = e >> 2;
+    const int g = f % G; f /= G;
+    const int kb = f % KB;
+    const int tap = f / KB;
+    const uint16_t* src = w + ((int64_t)tap * CIN + 4 * kb) * COUT + 4 * g + j;
+    wl[e] = u32x2_t{(uint32_t)src[0] | ((uint32_t)src[COUT] << 16), (uint32_t)src[2 * COUT] | ((uint32_t)src[3 * COUT] << 16)};
+  }
+  int64_t n = *d_n_out;
+  if (n > capacity_out) n = capacity_out;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t row0 = (int64_t)blockIdx.x * (4 * RG * 64) + (int64_t)wave * (RG * 64) + lane;
+  bool live[RG];
+  const int32_t* nrow[RG];
+  int32_t dead[RG];
+#pragma unroll
+  for (int r = 0; r < RG; ++r) {
+    live[r] = row0 + 64 * r < n;
+    nrow[r] = nbr + (live[r] ? row0 + 64 * r : 0);
+    dead[r] = live[r] ? 0 : -1;
+  }
+  unsigned long long oob = 0ull;
+  float4_t acc[RG][G];
+#pragma unroll
+  for (int r = 0; r < RG; ++r)
+#pragma unroll
+    for (int g = 0; g < G; ++g) acc[r][g] = float4_t{0.f, 0.f, 0.f, 0.f};
+  __syncthreads();   // weights in LDS
+  const int jq = lane & 3;
+  // all kernel-map entries of the wave's rows are requested at once, before the first of them is used
+  int32_t jall[RG][27];
+#pragma unroll
+  for (int r = 0; r < RG; ++r)
+#pragma unroll
+    for (int k = 0; k < 27; ++k) jall[r][k] = nrow[r][(int64_t)k * capacity_out];
+#pragma unroll
+  for (int k0 = 0; k0 < 27; k0 += TB) {
+    int32_t j[RG][TB];
+    uint32_t x[RG][TB][RW];
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+#pragma unroll
+      for (int t = 0; t < TB; ++t) {
+        j[r][t] = emc2_entry(jall[r][k0 + t], dead[r], n_in, oob);
+        const char* src = reinterpret_cast<const char*>(in + (int64_t)(j[r][t] >= 0 ? j[r][t] : 0) * CIN);
+        if constexpr (RW == 2) {
+          const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src);
+          x[r][t][0] = v.x; x[r][t][1] = v.y;
+        } else {
+#pragma unroll
+          for (int q = 0; q < RW / 4; ++q) {
+            const u32x4_t v = reinterpret_cast<const u32x4_t*>(src)[q];
+            x[r][t][4 * q] = v.x; x[r][t][4 * q + 1] = v.y; x[r][t][4 * q + 2] = v.z; x[r][t][4 * q + 3] = v.w;
+          }
+        }
+      }
+#pragma unroll
+    for (int t = 0; t < TB; ++t) {
+      bool have[RG];
+      unsigned long long any = 0ull;
+#pragma unroll
+      for (int r = 0; r < RG; ++r) {
+        have[r] = j[r][t] >= 0;
+        any |= __ballot(have[r]);
+      }
+      if (any == 0ull) continue;   // wave-uniform: nobody has this tap
+      const u32x2_t* wt = wl + (k0 + t) * KB * G * 4 + jq;
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        u32x2_t b[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+          b[r] = have[r] ? u32x2_t{x[r][t][2 * kb], x[r][t][2 * kb + 1]} : u32x2_t{0u, 0u};   // an absent neighbour adds zero
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          const u32x2_t a = wt[(kb * G + g) * 4];
+#pragma unroll
+          for (int r = 0; r < RG; ++r) acc[r][g] = Mma4<DT>::run(a, b[r], acc[r][g]);
+        }
+      }
+    }
+  }
+  emc2_report_oob(oob, dev_flags);
+  // lane l holds output channels 4g .. 4g+3 of its row in acc[r][g]
+#pragma unroll
+  for (int r = 0; r < RG; ++r) {
+    if (!live[r]) continue;
+    uint32_t y[COUT / 2];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = acc[r][g][i];
+        if (epilogue != EMC2_EPI_NONE) v[i] = fmaf(v[i], scale[4 * g + i], shift[4 * g + i]);
+        if (epilogue == EMC2_EPI_AFFINE_RELU) v[i] = v[i] > 0.f ? v[i] : 0.f;
+      }
+      y[2 * g] = Mma4<DT>::cvt2(v[0], v[1]);
+      y[2 * g + 1] = Mma4<DT>::cvt2(v[2], v[3]);
+    }
+    u32x4_t* dst = reinterpret_cast<u32x4_t*>(out + (row0 + 64 * r) * COUT);
+#pragma unroll
+    for (int q = 0; q < COUT / 8; ++q) dst[q] = u32x4_t{y[4 * q], y[4 * q + 1], y[4 * q + 2], y[4 * q + 3]};
+  }
+}
+
+template <int DT>
+bool launch_rows(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
+                 const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
+                 int cin, int cout, void* d_out, hipStream_t s) {
+#define EMC2_ROWS(CI, CO)                                                                                             \
+  if (cin == CI && cout == CO) {                                                                                      \
+    hipLaunchKernelGGL((k_spconv_rows<DT, CI, CO>), dim3((unsigned)emc2_div_up(capacity_out, 512)), dim3(256), 0, s,  \
+                       (const uint16_t*)d_in, (const uint16_t*)d_w, d_scale, d_shift, epilogue, d_nbr, d_n_out,       \
+                       capacity_out, n_in, dev_flags, (uint16_t*)d_out);                                              \
+    return true;                                                                                                      \
+  }
+  EMC2_ROWS(4, 16) EMC2_ROWS(4, 32) EMC2_ROWS(16, 16)
+#undef EMC2_ROWS
+  return false;
+}
+
 template <typename T>
 bool launch_small(const void* d_in, const void* d_w, const float* d_scale, const float* d_shift, int epilogue,
                   const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
@@ -184,7 +354,8 @@ extern "C" const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t
     if (!emc2_spconv_direct_supported(cin, cout)) return "k_spconv_mfma";
     return (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout)) ? "k_spconv_span" : "k_spconv_direct";
   }
-  return small_covers(cin, cout) ? "k_spconv_small" : "k_spconv_alu";
+  if (!small_covers(cin, cout)) return "k_spconv_alu";
+  return dtype == EMC2_F32 ? "k_spconv_small" : "k_spconv_rows";
 }
 
 extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, int32_t cin, int32_t cout,
@@ -255,6 +426,10 @@ extern "C" emc2_status emc2_spconv(emc2_ctx* ctx, emc2_dtype dtype, const void* 
                                 cin, cout, ctx->zero_row, d_out, s);
   } else if (dtype == EMC2_F32) {
     launch_alu<float>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags, cin, cout, d_out, s);
+  } else if (dtype == EMC2_F16 && launch_rows<EMC2_F16>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out,
+                                                        n_in, flags, cin, cout, d_out, s)) {
+  } else if (dtype == EMC2_BF16 && launch_rows<EMC2_BF16>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out,
+                                                          capacity_out, n_in, flags, cin, cout, d_out, s)) {
   } else if (dtype == EMC2_F16) {
     launch_alu<__half>(d_in, d_w, d_scale, d_shift, (int)epilogue, d_nbr, d_n_out, capacity_out, n_in, flags, cin, cout, d_out, s);
   } else {
