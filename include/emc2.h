@@ -350,6 +350,23 @@ emc2_status emc2_dispatch(emc2_ctx* ctx, const float* d_props, const int32_t* d_
                           int32_t* d_order, void* stream);
 
 /*
+ * Expert-grouped batching (paper Sec. 3.2: the dispatcher routes every scene to one expert, so each expert's
+ * network runs on the scenes routed to it).  From emc2_dispatch's outputs, the batch ids that make emc2_voxelize
+ * build expert `expert`'s batch out of a mixed batch of points:
+ *   d_slot [n_scenes] int32 (written for every scene): the scene's position inside its own expert's group, i.e. its
+ *          index in d_order minus the sizes of the groups before its expert's;
+ *   d_group_batch [n_points] int32: d_slot[scene] for a point whose scene runs on `expert`, else -1 (a batch id
+ *          emc2_voxelize drops), also for a scene id outside [0, n_scenes).
+ *   d_scene [n_points] int32 scene of each point, or NULL (all in scene 0); d_expert, d_order, d_counts as written
+ *   by emc2_dispatch for the same n_scenes.  Voxelizing with d_batch = d_group_batch and n_batch = n_scenes (or
+ *   the group's size, if the host knows it) yields the group's scenes as frames 0 .. count-1 in ascending scene
+ *   order.  Integer results, exact.
+ */
+emc2_status emc2_group_points(emc2_ctx* ctx, const int32_t* d_scene, int64_t n_points, const int32_t* d_expert,
+                              const int32_t* d_order, const int32_t* d_counts, int32_t n_scenes, int32_t expert,
+                              int32_t* d_slot, int32_t* d_group_batch, void* stream);
+
+/*
  * Point -> image projection with bilinear feature gather (paper Sec. 3.1: image features are
  * aligned with 3D positions for fusion; Fig. 5 caption: sites without a match get zero-filled
  * features).

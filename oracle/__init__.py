@@ -56,6 +56,8 @@ def _load():
                                      vp, vp]
     lib.emc2o_fuse.restype = c_i64
     lib.emc2o_fuse.argtypes = [vp, vp, c_i64, c_i32, vp, vp, c_i64, c_i32, vp, c_i32, c_i64, vp, vp, vp, vp]
+    lib.emc2o_group_points.restype = c_i32
+    lib.emc2o_group_points.argtypes = [vp, c_i64, vp, vp, vp, c_i32, c_i32, vp, vp]
     lib.emc2o_quantize_i8.restype = c_i32
     lib.emc2o_quantize_i8.argtypes = [vp, c_i64, c_f, vp]
     lib.emc2o_spconv_i8.restype = c_i64
@@ -253,6 +255,25 @@ def dispatch(props: np.ndarray, scene: Optional[np.ndarray], n_scenes: int, dist
     _chk(lib.emc2o_dispatch(_p(props), _p(scene), n, int(n_scenes), float(np.float32(dist)), float(np.float32(conf)),
                             _p(expert), _p(counts), _p(order)), "dispatch")
     return expert[:n_scenes].copy(), counts, order[:n_scenes].copy()
+
+
+def group_points(scene: Optional[np.ndarray], n_points: int, expert: np.ndarray, order: np.ndarray, counts: np.ndarray,
+                 e: int):
+    """Dispatcher outputs -> (slot[S], group_batch[P]): every scene's position inside its expert's group, and the batch
+    ids of the points for expert e's group (-1 for points of other experts' scenes)."""
+    lib = _load()
+    expert = np.ascontiguousarray(expert, dtype=np.int32)
+    order = np.ascontiguousarray(order, dtype=np.int32)
+    counts = np.ascontiguousarray(counts, dtype=np.int32)
+    n_scenes = len(expert)
+    if scene is not None:
+        scene = np.ascontiguousarray(scene, dtype=np.int32)
+        assert len(scene) == n_points
+    slot = np.empty((n_scenes,), np.int32)
+    gb = np.empty((n_points,), np.int32)
+    _chk(lib.emc2o_group_points(_p(scene), int(n_points), _p(expert), _p(order), _p(counts), n_scenes, int(e), _p(slot), _p(gb)),
+         "group_points")
+    return slot, gb
 
 
 def spconv(x: np.ndarray, w: np.ndarray, scale: Optional[np.ndarray], shift: Optional[np.ndarray],

@@ -23,7 +23,8 @@
  *   - multimodal fusion (Sec. 3.1, Fig. 5 caption): the union of LiDAR voxels and pooled image cells,
  *     features concatenated, the missing half zero-filled;
  *   - Scenario-Adaptive Dispatcher (Sec. 3.2): one of three experts per scene from the distances and
- *     confidences of its proposal regions, and the scenes grouped by expert;
+ *     confidences of its proposal regions, the scenes grouped by expert, and the batch ids of the points for
+ *     the group of one expert;
  *   - quantised sparse convolution (Sec. 3.6 (2) names model quantisation without giving a scheme; the
  *     scheme here is this build's own): int8 features and weights, exact integer accumulation, a
  *     per-channel fp32 multiply-add, optional ReLU, optional re-quantisation to int8.
@@ -504,6 +505,35 @@ int32_t emc2o_dispatch(const float* props, const int32_t* scene, int64_t n, int3
   for (int32_t s = 0; s < n_scenes; ++s) counts[expert[s]]++;
   int32_t at[3] = {0, counts[0], counts[0] + counts[1]};
   for (int32_t s = 0; s < n_scenes; ++s) order[at[expert[s]]++] = s;
+  return 0;
+}
+
+/*
+ * Expert-grouped batching (Sec. 3.2: every scene is routed to one expert, so each expert's network runs on the
+ * scenes routed to it).  Given the dispatcher's outputs, the points of the batch get the batch ids of expert e's
+ * group: slot[s] = position of scene s inside its expert's part of `order` (for every scene, whatever its expert);
+ * group_batch[i] = slot[scene[i]] if scene i's expert is e, else -1 (the voxelizer drops such points; also for a
+ * scene id outside [0, n_scenes)).  Written the slow way: the position is found by searching `order`.
+ * Returns 0 or a negative error (an `order` that is not a grouping of the scenes by `expert`).
+ */
+int32_t emc2o_group_points(const int32_t* scene, int64_t n_points, const int32_t* expert, const int32_t* order,
+                           const int32_t* counts, int32_t n_scenes, int32_t e, int32_t* slot, int32_t* group_batch) {
+  if (n_scenes < 1 || n_points < 0 || e < 0 || e > 2) return EMC2O_ERR_ARG;
+  if (counts[0] < 0 || counts[1] < 0 || counts[2] < 0 || counts[0] + counts[1] + counts[2] != n_scenes) return EMC2O_ERR_ARG;
+  for (int32_t s = 0; s < n_scenes; ++s) {
+    if (expert[s] < 0 || expert[s] > 2) return EMC2O_ERR_ARG;
+    int32_t start = 0;
+    for (int32_t x = 0; x < expert[s]; ++x) start += counts[x];
+    int32_t found = -1;
+    for (int32_t p = start; p < start + counts[expert[s]]; ++p)
+      if (order[p] == s) { found = p - start; break; }
+    if (found < 0) return EMC2O_ERR_ARG;
+    slot[s] = found;
+  }
+  for (int64_t i = 0; i < n_points; ++i) {
+    const int32_t s = scene ? scene[i] : 0;
+    group_batch[i] = (s >= 0 && s < n_scenes && expert[s] == e) ? slot[s] : -1;
+  }
   return 0;
 }
 

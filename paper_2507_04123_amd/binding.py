@@ -30,7 +30,7 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
            "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch", "emc2_spconv_i8_supported",
-           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8", "emc2_build_kmap_static"]
+           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8", "emc2_build_kmap_static", "emc2_group_points"]
 
 
 class Emc2Error(RuntimeError):
@@ -98,6 +98,8 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_spconv_i8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, ctypes.c_float, vp, vp, i64, i64, i32, i32, vp, vp]
     lib.emc2_dispatch.restype = ctypes.c_int
     lib.emc2_dispatch.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
+    lib.emc2_group_points.restype = ctypes.c_int
+    lib.emc2_group_points.argtypes = [vp, vp, i64, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.emc2_project_gather.restype = ctypes.c_int
     lib.emc2_project_gather.argtypes = [vp, vp, i32, i64, ctypes.POINTER(ctypes.c_float), vp, i32, i32, i32, vp, vp, vp, vp]
     lib.emc2_build_inverse_kmap.restype = ctypes.c_int
@@ -424,6 +426,21 @@ class Context:
         self._chk(self.lib.emc2_spconv(self.h, dtype, _ptr(x), _ptr(w), w_layout, _ptr(scale), _ptr(shift), epilogue, _ptr(nbr),
                                        map_hint, _ptr(n_out), capacity_out,
                                        int(x.shape[0]) if n_in_rows is None else n_in_rows, cin, cout, _ptr(out), _stream()))
+
+    def group_points(self, scene: Optional[torch.Tensor], n_points: int, expert: torch.Tensor, order: torch.Tensor,
+                     counts: torch.Tensor, n_scenes: int, e: int, slot: torch.Tensor, group_batch: torch.Tensor) -> None:
+        """Dispatcher outputs -> slot[n_scenes] and, for expert e, group_batch[n_points] (-1 for other experts' points)."""
+        for t, nm in ((expert, "expert"), (order, "order"), (counts, "counts"), (slot, "slot"), (group_batch, "group_batch")):
+            _dev_check(t, torch.int32, nm)
+        if scene is not None:
+            _dev_check(scene, torch.int32, "scene")
+            if scene.numel() != n_points:
+                raise ValueError("scene length != n_points")
+        if expert.numel() < n_scenes or order.numel() < n_scenes or counts.numel() < 3 or slot.numel() < n_scenes or \
+                group_batch.numel() < n_points:
+            raise ValueError("buffers smaller than n_scenes / n_points")
+        self._chk(self.lib.emc2_group_points(self.h, _ptr(scene), n_points, _ptr(expert), _ptr(order), _ptr(counts), n_scenes,
+                                             e, _ptr(slot), _ptr(group_batch), _stream()))
 
     def project_gather(self, points: torch.Tensor, pmat: Sequence[float], img: torch.Tensor, out: torch.Tensor,
                        valid: torch.Tensor, uv: Optional[torch.Tensor] = None) -> None:

@@ -111,6 +111,18 @@ def make_configs() -> List[Config]:
     return [c1, c2, c3, c4, c5]
 
 
+def expert_branches(n_scenes: int) -> Tuple[Branch, Branch, Branch]:
+    """Stand-ins for the LiDAR stacks of the three experts a scene can be routed to (paper Sec. 3.2 / 3.3), indexed
+    by expert id: the latency-prioritised expert works on coarse voxels with a short stack, the versatile one on
+    fine voxels with two stages, the accuracy-prioritised one on fine voxels with the full three-stage backbone.
+    Each runs on a batch of up to n_scenes scenes (the scenes the dispatcher routes to it)."""
+    lpe = Branch("lpe", _front_spec(2, n_batch=n_scenes), (Layer(SUBM, 4, 32),) + _stage(32, 64))
+    vee = Branch("vee", _front_spec(1, n_batch=n_scenes), (Layer(SUBM, 4, 16),) + _stage(16, 32) + _stage(32, 64))
+    ape = Branch("ape", _front_spec(1, n_batch=n_scenes),
+                 (Layer(SUBM, 4, 16),) + _stage(16, 32) + _stage(32, 64) + _stage(64, 64))
+    return (lpe, vee, ape)
+
+
 CONFIGS = make_configs()
 
 

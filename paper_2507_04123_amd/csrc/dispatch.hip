@@ -114,7 +114,48 @@ __global__ void __launch_bounds__(1024) k_dispatch_group(const int32_t* __restri
   group_scenes(expert, n_scenes, counts, order);
 }
 
+// Expert-grouped batching.  Position p of `order` holds scene s: its slot inside its expert's group is p minus the
+// group's start (the counts of the experts before it).
+__global__ void __launch_bounds__(256) k_group_slots(const int32_t* __restrict__ expert, const int32_t* __restrict__ order,
+                                                     const int32_t* __restrict__ counts, int n_scenes,
+                                                     int32_t* __restrict__ slot) {
+  const int p = blockIdx.x * blockDim.x + threadIdx.x;
+  if (p >= n_scenes) return;
+  const int32_t s = order[p];
+  if (s < 0 || s >= n_scenes) return;   // malformed order: leave the slot as it is rather than write out of bounds
+  const int32_t e = expert[s];
+  const int32_t start = e <= 0 ? 0 : (e == 1 ? counts[0] : counts[0] + counts[1]);
+  slot[s] = p - start;
+}
+
+// One thread per point: the slot of its scene if that scene runs on `e`, else -1 (the voxelizer drops the point).
+__global__ void __launch_bounds__(256) k_group_points(const int32_t* __restrict__ scene, int64_t n_points,
+                                                      const int32_t* __restrict__ expert, const int32_t* __restrict__ slot,
+                                                      int n_scenes, int e, int32_t* __restrict__ group_batch) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_points) return;
+  const int32_t s = scene ? scene[i] : 0;
+  group_batch[i] = (s >= 0 && s < n_scenes && expert[s] == e) ? slot[s] : -1;
+}
+
 }  // namespace
+
+extern "C" emc2_status emc2_group_points(emc2_ctx* ctx, const int32_t* d_scene, int64_t n_points, const int32_t* d_expert,
+                                         const int32_t* d_order, const int32_t* d_counts, int32_t n_scenes, int32_t expert,
+                                         int32_t* d_slot, int32_t* d_group_batch, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (!d_expert || !d_order || !d_counts || !d_slot || (n_points > 0 && !d_group_batch))
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_group_points: null argument");
+  if (n_points < 0 || n_scenes < 1 || n_scenes > (1 << 20) || expert < 0 || expert > 2)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_group_points: n_points < 0, n_scenes outside [1, 2^20] or expert outside [0, 2]");
+  hipStream_t s = (hipStream_t)stream;
+  hipLaunchKernelGGL(k_group_slots, dim3((unsigned)emc2_div_up(n_scenes, 256)), dim3(256), 0, s, d_expert, d_order, d_counts,
+                     n_scenes, d_slot);
+  if (n_points > 0)
+    hipLaunchKernelGGL(k_group_points, dim3((unsigned)emc2_div_up(n_points, 256)), dim3(256), 0, s, d_scene, n_points, d_expert,
+                       d_slot, n_scenes, expert, d_group_batch);
+  return emc2_check_hip(ctx, hipGetLastError(), "emc2_group_points launch");
+}
 
 extern "C" emc2_status emc2_dispatch(emc2_ctx* ctx, const float* d_props, const int32_t* d_scene, int64_t n_props,
                                      int32_t n_scenes, float dist, float conf, int32_t* d_expert, int32_t* d_counts,

@@ -374,3 +374,47 @@ class ConfigRunner:
         for s in self.side:
             main.wait_stream(s)
         return self.graph_out
+
+
+class RoutedRunner:
+    """Scene-level routing (paper Sec. 3.2): the dispatcher picks an expert per scene from the scene's proposal
+    regions, the scenes are grouped by expert, and each expert's stack runs on its own group only.  Sequencing
+    only: emc2_dispatch -> per expert emc2_group_points -> that expert's BranchRunner with the group's batch ids
+    (points of other experts' scenes carry -1 and are dropped by the voxelizer).  Group sizes stay on the device:
+    every expert's buffers are sized for all n_scenes, and nothing here waits for the host."""
+
+    def __init__(self, experts: Sequence[Branch], dtype: int, n_points: int, n_scenes: int, seed: int, device: str = "cuda"):
+        self.n_points, self.n_scenes = n_points, n_scenes
+        i32 = dict(dtype=torch.int32, device=device)
+        self.expert = torch.zeros((n_scenes,), **i32)
+        self.counts = torch.zeros((3,), **i32)
+        self.order = torch.zeros((n_scenes,), **i32)
+        self.slot = torch.zeros((n_scenes,), **i32)
+        self.runners: List[Tuple[B.Context, BranchRunner]] = []
+        self.group_batch: List[torch.Tensor] = []
+        for e, br in enumerate(experts):
+            assert br.spec.n_batch == n_scenes
+            caps = default_capacities(br, n_points)
+            ctx = B.Context(n_points, max(caps), cells_of(br.spec.grid, n_scenes), n_slots=len(caps))
+            self.runners.append((ctx, BranchRunner(ctx, br, dtype, n_points, device_params(br.layers, seed + e, dtype),
+                                                   capacities=caps, device=device)))
+            self.group_batch.append(torch.empty((n_points,), **i32))
+
+    def close(self) -> None:
+        for ctx, _ in self.runners:
+            ctx.close()
+
+    def status_sync(self) -> None:
+        for ctx, _ in self.runners:
+            ctx.status_sync()
+
+    def run(self, points: torch.Tensor, scene: torch.Tensor, props: torch.Tensor, prop_scene: Optional[torch.Tensor],
+            dist: float, conf: float) -> List[torch.Tensor]:
+        ctx0 = self.runners[0][0]
+        ctx0.dispatch(props, prop_scene, self.n_scenes, dist, conf, self.expert, self.counts, self.order)
+        outs = []
+        for e, (ctx, r) in enumerate(self.runners):
+            ctx.group_points(scene, self.n_points, self.expert, self.order, self.counts, self.n_scenes, e, self.slot,
+                             self.group_batch[e])
+            outs.append(r.run(points, self.group_batch[e]))
+        return outs

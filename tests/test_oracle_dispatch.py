@@ -106,3 +106,54 @@ def test_invariants():
     assert np.all(e_all[has] == APE) and np.all(e_all[~has] == LPE)
     with pytest.raises(RuntimeError):
         oracle.dispatch(props, scene, n_scenes, -1.0, c)
+
+
+# ------------------------------------------------------------------------------------------------
+# expert-grouped batching: the batch ids of the points for one expert's group
+# ------------------------------------------------------------------------------------------------
+
+def test_group_points_hand_case():
+    """Five scenes, experts (1, 0, 2, 0, 1): the groups are LPE {1, 3}, VEE {0, 4}, APE {2}; a scene's slot is its
+    place inside its own group, and a point gets its scene's slot only in the call for that scene's expert."""
+    expert = np.array([1, 0, 2, 0, 1], np.int32)
+    counts = np.array([2, 2, 1], np.int32)
+    order = np.array([1, 3, 0, 4, 2], np.int32)
+    scene = np.array([0, 1, 2, 3, 4, 4, 3, 7, -1, 0], np.int32)     # two ids outside the batch
+    slot, gb0 = oracle.group_points(scene, len(scene), expert, order, counts, LPE)
+    assert slot.tolist() == [0, 0, 0, 1, 1]
+    assert gb0.tolist() == [-1, 0, -1, 1, -1, -1, 1, -1, -1, -1]
+    _, gb1 = oracle.group_points(scene, len(scene), expert, order, counts, VEE)
+    assert gb1.tolist() == [0, -1, -1, -1, 1, 1, -1, -1, -1, 0]
+    _, gb2 = oracle.group_points(scene, len(scene), expert, order, counts, APE)
+    assert gb2.tolist() == [-1, -1, 0, -1, -1, -1, -1, -1, -1, -1]
+    # no scene array: every point belongs to scene 0
+    _, g = oracle.group_points(None, 3, expert, order, counts, VEE)
+    assert g.tolist() == [0, 0, 0]
+    # an order that is not the grouping of these experts is refused
+    with pytest.raises(RuntimeError):
+        oracle.group_points(scene, len(scene), expert, np.array([1, 0, 3, 4, 2], np.int32), counts, LPE)
+
+
+@pytest.mark.parametrize("n_scenes,seed", [(8, 3), (200, 4)])
+def test_group_points_invariants_on_dispatcher_output(n_scenes, seed):
+    """On the dispatcher's own output: the three calls partition the points of valid scenes; inside one group the
+    slots are 0 .. count-1, ascending with the scene index; regrouping by slot reproduces `order`."""
+    props, pscene = gen.make_proposals(n_scenes, seed)
+    expert, counts, order = oracle.dispatch(props, pscene, n_scenes, 23.5, 0.5)
+    st = gen.Stream(seed, 77)
+    scene = (st.bits(5000) % np.uint64(n_scenes + 2)).astype(np.int32) - 1          # ids -1 .. n_scenes
+    gbs = []
+    for e in (LPE, VEE, APE):
+        slot, gb = oracle.group_points(scene, len(scene), expert, order, counts, e)
+        gbs.append(gb)
+        mine = np.flatnonzero(expert == e)
+        assert sorted(slot[mine].tolist()) == list(range(counts[e]))
+        assert np.all(np.diff(slot[mine]) > 0)                                       # ascending scene index inside a group
+        start = int(counts[:e].sum())
+        assert np.array_equal(order[start + slot[mine]], mine)
+        valid = (scene >= 0) & (scene < n_scenes)
+        want = np.where(valid & (expert[np.clip(scene, 0, n_scenes - 1)] == e), slot[np.clip(scene, 0, n_scenes - 1)], -1)
+        assert np.array_equal(gb, want)
+    taken = np.stack(gbs) >= 0
+    valid = (scene >= 0) & (scene < n_scenes)
+    assert np.array_equal(taken.sum(axis=0), valid.astype(np.int64))                 # exactly one expert per valid point
