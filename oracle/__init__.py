@@ -56,6 +56,12 @@ def _load():
                                      vp, vp]
     lib.emc2o_fuse.restype = c_i64
     lib.emc2o_fuse.argtypes = [vp, vp, c_i64, c_i32, vp, vp, c_i64, c_i32, vp, c_i32, c_i64, vp, vp, vp, vp]
+    lib.emc2o_e4m3_value.restype = ctypes.c_double
+    lib.emc2o_e4m3_value.argtypes = [ctypes.c_uint8]
+    lib.emc2o_quantize_e4m3.restype = c_i32
+    lib.emc2o_quantize_e4m3.argtypes = [vp, c_i64, c_f, vp]
+    lib.emc2o_spconv_e4m3.restype = c_i64
+    lib.emc2o_spconv_e4m3.argtypes = [vp, c_i64, vp, vp, vp, c_i32, vp, c_i64, c_i64, c_i32, c_i32, vp]
     lib.emc2o_group_points.restype = c_i32
     lib.emc2o_group_points.argtypes = [vp, c_i64, vp, vp, vp, c_i32, c_i32, vp, vp]
     lib.emc2o_quantize_i8.restype = c_i32
@@ -235,6 +241,39 @@ def spconv_i8(xq: np.ndarray, wq: np.ndarray, mul: np.ndarray, add: np.ndarray, 
                              float(np.float32(inv_out_scale if inv_out_scale is not None else 0.0)), _p(nbr),
                              max(n_out, 0), n_out, cin, cout, _p(v), _p(q)), "spconv_i8")
     return (v, q) if inv_out_scale is not None else v
+
+
+def e4m3_value(code: int) -> float:
+    """Value of one E4M3 code (NaN for the two codes that are not numbers)."""
+    return float(_load().emc2o_e4m3_value(int(code) & 0xFF))
+
+
+def quantize_e4m3(x: np.ndarray, inv_scale: float) -> np.ndarray:
+    """fp32 -> E4M3 codes (uint8): nearest finite value of fl(x * inv_scale), ties to even, saturating, NaN -> 0."""
+    lib = _load()
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.shape, np.uint8)
+    _chk(lib.emc2o_quantize_e4m3(_p(x), x.size, float(np.float32(inv_scale)), _p(q)), "quantize_e4m3")
+    return q
+
+
+def spconv_e4m3(xq: np.ndarray, wq: np.ndarray, mul: np.ndarray, add: np.ndarray, relu: bool, nbr: np.ndarray) -> np.ndarray:
+    """uint8 E4M3 codes x[n][Cin], w[27][Cin][Cout], fp32 mul/add[Cout], nbr[27][V] -> v[V][Cout] f32: exact accumulation
+    of the exact products, one rounding to fp32, v = fl(fl(acc * mul) + add), optional ReLU."""
+    lib = _load()
+    xq = np.ascontiguousarray(xq, dtype=np.uint8)
+    wq = np.ascontiguousarray(wq, dtype=np.uint8)
+    mul = np.ascontiguousarray(mul, dtype=np.float32)
+    add = np.ascontiguousarray(add, dtype=np.float32)
+    nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+    n_in, cin = xq.shape
+    assert wq.shape[0] == 27 and wq.shape[1] == cin and nbr.shape[0] == 27
+    cout = wq.shape[2]
+    n_out = nbr.shape[1]
+    v = np.empty((n_out, cout), np.float32)
+    _chk(lib.emc2o_spconv_e4m3(_p(xq), n_in, _p(wq), _p(mul), _p(add), int(bool(relu)), _p(nbr), max(n_out, 0), n_out, cin, cout,
+                               _p(v)), "spconv_e4m3")
+    return v
 
 
 LPE, VEE, APE = 0, 1, 2

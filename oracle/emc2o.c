@@ -27,7 +27,8 @@
  *     the group of one expert;
  *   - quantised sparse convolution (Sec. 3.6 (2) names model quantisation without giving a scheme; the
  *     scheme here is this build's own): int8 features and weights, exact integer accumulation, a
- *     per-channel fp32 multiply-add, optional ReLU, optional re-quantisation to int8.
+ *     per-channel fp32 multiply-add, optional ReLU, optional re-quantisation to int8; and the same with 8-bit
+ *     floating-point (E4M3) features and weights, whose products and sums are exact in fp64.
  *
  * Compile: gcc -O2 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math: the cell index is
  * defined by IEEE fp32 subtract, divide, floor).
@@ -652,6 +653,95 @@ int64_t emc2o_spconv_i8(const int8_t* xq, int64_t n_in, const int8_t* wq, const 
       if (relu && !(v > 0.0f)) v = 0.0f;
       out_v[o * cout + cc] = v;
       if (out_q) out_q[o * cout + cc] = quant_i8(v, inv_out_scale);
+    }
+  free(acc);
+  return macs;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* fp8 (E4M3) sparse convolution                                                               */
+/* ------------------------------------------------------------------------------------------- */
+
+/*
+ * The 8-bit floating-point format used here is E4M3 without infinities (1 sign bit, 4 exponent bits with bias 7,
+ * 3 mantissa bits): code s.eeee.mmm is (-1)^s 2^(e-7) (1 + m/8) for e > 0 and (-1)^s 2^(-6) (m/8) for e = 0; the two
+ * codes with all exponent and mantissa bits set are not numbers; the largest finite value is 448 (code 0x7E).
+ */
+double emc2o_e4m3_value(uint8_t code) {
+  const int s = code >> 7, e = (code >> 3) & 15, m = code & 7;
+  if (e == 15 && m == 7) return NAN;
+  const double mag = e > 0 ? ldexp(1.0 + m / 8.0, e - 7) : ldexp(m / 8.0, -6);
+  return s ? -mag : mag;
+}
+
+/*
+ * Quantiser: the finite E4M3 value nearest to t = fl(x * inv_scale) (the product rounded to fp32), ties to the code
+ * with an even mantissa, |t| beyond 448 (also infinities) saturating to +-448, NaN -> +0; zero keeps its sign bit clear
+ * (-0 and values that round to zero give code 0x00).  Written as a search over the 127 positive codes: no bit tricks.
+ */
+static uint8_t quant_e4m3(float x, float inv_scale) {
+  volatile float tf = x * inv_scale;
+  const double t = (double)tf;
+  if (!(t == t)) return 0;
+  const double a = fabs(t);
+  int best = 0;
+  double best_d = a; /* distance to code 0 */
+  for (int c = 1; c <= 0x7E; ++c) {
+    const double d = fabs(a - emc2o_e4m3_value((uint8_t)c));
+    if (d < best_d || (d == best_d && (c & 1) == 0)) { best = c; best_d = d; }
+  }
+  if (best == 0) return 0;
+  return (uint8_t)(best | (t < 0 ? 0x80 : 0));
+}
+
+int32_t emc2o_quantize_e4m3(const float* x, int64_t n, float inv_scale, uint8_t* q) {
+  if (n < 0) return EMC2O_ERR_ARG;
+  for (int64_t i = 0; i < n; ++i) q[i] = quant_e4m3(x[i], inv_scale);
+  return 0;
+}
+
+/*
+ * acc[o][c'] = sum over taps k with nbr[k][o] >= 0, sum over c: value(xq[nbr[k][o]][c]) * value(wq[k][c][c']), in fp64
+ * (every product of two E4M3 values is exact there, and so is a sum of a few thousand of them), rounded once to
+ * fp32; then, as in the int8 scheme, v = fl(fl(acc * mul[c']) + add[c']) with separately rounded product and sum,
+ * relu: v = max(v, 0).  A code that is not a number anywhere in xq or wq is an error.  Returns the number of
+ * multiply-accumulates, or a negative error.
+ */
+int64_t emc2o_spconv_e4m3(const uint8_t* xq, int64_t n_in, const uint8_t* wq, const float* mul, const float* add,
+                          int32_t relu, const int32_t* nbr, int64_t nbr_stride, int64_t n_out, int32_t cin, int32_t cout,
+                          float* out_v) {
+  if (n_out < 0 || n_out > nbr_stride || cin < 1 || cout < 1 || !mul || !add) return EMC2O_ERR_ARG;
+  for (int64_t i = 0; i < n_in * cin; ++i)
+    if ((xq[i] & 0x7F) == 0x7F) return EMC2O_ERR_ARG;
+  for (int64_t i = 0; i < (int64_t)27 * cin * cout; ++i)
+    if ((wq[i] & 0x7F) == 0x7F) return EMC2O_ERR_ARG;
+  double* acc = (double*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)cout, sizeof(double));
+  if (!acc) return EMC2O_ERR_NOMEM;
+  int64_t macs = 0;
+  for (int k = 0; k < 27; ++k) {
+    const uint8_t* wk = wq + (int64_t)k * cin * cout;
+    for (int64_t o = 0; o < n_out; ++o) {
+      const int32_t j = nbr[(int64_t)k * nbr_stride + o];
+      if (j < 0) continue;
+      if (j >= n_in) { free(acc); return EMC2O_ERR_ARG; }
+      const uint8_t* xr = xq + (int64_t)j * cin;
+      double* ar = acc + o * cout;
+      for (int c = 0; c < cin; ++c) {
+        const double xv = emc2o_e4m3_value(xr[c]);
+        const uint8_t* wr = wk + (int64_t)c * cout;
+        for (int cc = 0; cc < cout; ++cc) ar[cc] += xv * emc2o_e4m3_value(wr[cc]);
+      }
+      macs += (int64_t)cin * cout;
+    }
+  }
+  for (int64_t o = 0; o < n_out; ++o)
+    for (int cc = 0; cc < cout; ++cc) {
+      const float a = (float)acc[o * cout + cc];
+      volatile float p = a * mul[cc];
+      volatile float sum = p + add[cc];
+      float v = sum;
+      if (relu && !(v > 0.0f)) v = 0.0f;
+      out_v[o * cout + cc] = v;
     }
   free(acc);
   return macs;
