@@ -329,6 +329,29 @@ emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const void* d_w_pa
                            const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows, int32_t cin,
                            int32_t cout, void* d_out, void* stream);
 
+/*
+ * The same quantised convolution with 8-bit floating-point operands (paper Sec. 3.6 (2) again; the scheme is the
+ * library's own).  Format: E4M3 -- 1 sign, 4 exponent (bias 7), 3 mantissa bits, no infinities, largest value 448,
+ * the two codes with all exponent and mantissa bits set are not numbers and must not occur in the operands.
+ *   acc[o][c'] = sum_{k : nbr[k][o] >= 0} sum_c value(xq[nbr[k][o]][c]) * value(wq[k][c][c'])   products exact, sums fp32
+ *   v          = fl(fl(acc * mul[c']) + add[c']);  v = max(v, 0) if relu;  out = v as F32, or rounded to F16
+ * The products are exact; the accumulation is the matrix cores' own (the 32 products of one instruction are aligned
+ * to the largest before they are added, which drops low bits), so the result agrees with the exactly accumulated one
+ * to a few 1e-4 of the output's magnitude when the operands span the format's range, and exactly when every partial
+ * sum is a small integer.
+ *   d_in [n_in][Cin] uint8 codes; d_w_packed: the [27][Cin][Cout] codes re-ordered by emc2_pack_weights_i8 (a byte
+ *   permutation, whatever the bytes encode); shapes, d_nbr, d_n_out, capacity_out, n_in_rows, alignment as for
+ *   emc2_spconv_i8.
+ * emc2_quantize_e4m3: q[i] = the finite code nearest to fl((float)x[i] * inv_scale), ties to the even code, beyond 448
+ * (and infinities) saturating, NaN -> 0, zero always +0; x of F32 or F16.  Exact (byte results).
+ */
+emc2_status emc2_quantize_e4m3(emc2_ctx* ctx, emc2_dtype dtype, const void* d_x, int64_t n, float inv_scale, uint8_t* d_q,
+                               void* stream);
+emc2_status emc2_spconv_e4m3(emc2_ctx* ctx, const uint8_t* d_in, const void* d_w_packed, const float* d_mul,
+                             const float* d_add, int32_t relu, emc2_dtype out_dtype, const int32_t* d_nbr,
+                             const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows, int32_t cin, int32_t cout,
+                             void* d_out, void* stream);
+
 typedef enum { EMC2_EXPERT_LPE = 0, EMC2_EXPERT_VEE = 1, EMC2_EXPERT_APE = 2 } emc2_expert;
 
 /*

@@ -715,25 +715,37 @@ int64_t emc2o_spconv_e4m3(const uint8_t* xq, int64_t n_in, const uint8_t* wq, co
     if ((xq[i] & 0x7F) == 0x7F) return EMC2O_ERR_ARG;
   for (int64_t i = 0; i < (int64_t)27 * cin * cout; ++i)
     if ((wq[i] & 0x7F) == 0x7F) return EMC2O_ERR_ARG;
+  /* decode every operand once (each code to its value), then the plain loops */
   double* acc = (double*)calloc((size_t)(n_out > 0 ? n_out : 1) * (size_t)cout, sizeof(double));
-  if (!acc) return EMC2O_ERR_NOMEM;
+  double* xv = (double*)malloc(sizeof(double) * (size_t)(n_in > 0 ? n_in : 1) * (size_t)cin);
+  double* wv = (double*)malloc(sizeof(double) * (size_t)27 * cin * cout);
+  if (!acc || !xv || !wv) { free(acc); free(xv); free(wv); return EMC2O_ERR_NOMEM; }
+  for (int64_t i = 0; i < n_in * cin; ++i) xv[i] = emc2o_e4m3_value(xq[i]);
+  for (int64_t i = 0; i < (int64_t)27 * cin * cout; ++i) wv[i] = emc2o_e4m3_value(wq[i]);
   int64_t macs = 0;
+  int bad = 0;
   for (int k = 0; k < 27; ++k) {
-    const uint8_t* wk = wq + (int64_t)k * cin * cout;
+    const double* wk = wv + (int64_t)k * cin * cout;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) reduction(+ : macs) reduction(| : bad)
+#endif
     for (int64_t o = 0; o < n_out; ++o) {
       const int32_t j = nbr[(int64_t)k * nbr_stride + o];
       if (j < 0) continue;
-      if (j >= n_in) { free(acc); return EMC2O_ERR_ARG; }
-      const uint8_t* xr = xq + (int64_t)j * cin;
+      if (j >= n_in) { bad |= 1; continue; }
+      const double* xr = xv + (int64_t)j * cin;
       double* ar = acc + o * cout;
       for (int c = 0; c < cin; ++c) {
-        const double xv = emc2o_e4m3_value(xr[c]);
-        const uint8_t* wr = wk + (int64_t)c * cout;
-        for (int cc = 0; cc < cout; ++cc) ar[cc] += xv * emc2o_e4m3_value(wr[cc]);
+        const double x1 = xr[c];
+        const double* wr = wk + (int64_t)c * cout;
+        for (int cc = 0; cc < cout; ++cc) ar[cc] += x1 * wr[cc];
       }
       macs += (int64_t)cin * cout;
     }
   }
+  free(xv);
+  free(wv);
+  if (bad) { free(acc); return EMC2O_ERR_ARG; }
   for (int64_t o = 0; o < n_out; ++o)
     for (int cc = 0; cc < cout; ++cc) {
       const float a = (float)acc[o * cout + cc];

@@ -30,7 +30,7 @@ _TORCH_DTYPE = {F32: torch.float32, F16: torch.float16, BF16: torch.bfloat16}
 EXPORTS = ["emc2_create", "emc2_destroy", "emc2_status_sync", "emc2_last_error", "emc2_voxelize",
            "emc2_build_kmap", "emc2_spconv", "emc2_project_gather", "emc2_pack_weights", "emc2_spconv_uses_mfma",
            "emc2_spconv_kernel", "emc2_build_inverse_kmap", "emc2_bev_flatten", "emc2_pool_image", "emc2_fuse", "emc2_dispatch", "emc2_spconv_i8_supported",
-           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8", "emc2_build_kmap_static", "emc2_group_points"]
+           "emc2_quantize_i8", "emc2_pack_weights_i8", "emc2_spconv_i8", "emc2_build_kmap_static", "emc2_group_points", "emc2_quantize_e4m3", "emc2_spconv_e4m3"]
 
 
 class Emc2Error(RuntimeError):
@@ -96,6 +96,10 @@ def load_library() -> ctypes.CDLL:
     lib.emc2_pack_weights_i8.argtypes = [vp, vp, i32, i32, vp, vp]
     lib.emc2_spconv_i8.restype = ctypes.c_int
     lib.emc2_spconv_i8.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, ctypes.c_float, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.emc2_quantize_e4m3.restype = ctypes.c_int
+    lib.emc2_quantize_e4m3.argtypes = [vp, ctypes.c_int, vp, i64, ctypes.c_float, vp, vp]
+    lib.emc2_spconv_e4m3.restype = ctypes.c_int
+    lib.emc2_spconv_e4m3.argtypes = [vp, vp, vp, vp, vp, i32, ctypes.c_int, vp, vp, i64, i64, i32, i32, vp, vp]
     lib.emc2_dispatch.restype = ctypes.c_int
     lib.emc2_dispatch.argtypes = [vp, vp, vp, i64, i32, ctypes.c_float, ctypes.c_float, vp, vp, vp, vp]
     lib.emc2_group_points.restype = ctypes.c_int
@@ -385,6 +389,37 @@ class Context:
                                           I8 if out.dtype == torch.int8 else F16, inv_out_scale, _ptr(nbr), _ptr(n_out),
                                           capacity_out, int(x.shape[0]) if n_in_rows is None else n_in_rows, cin, cout,
                                           _ptr(out), _stream()))
+
+    def quantize_e4m3(self, x: torch.Tensor, inv_scale: float, q: torch.Tensor) -> None:
+        """q[i] = E4M3 code (uint8) nearest to x[i] * inv_scale; x float32 or float16."""
+        if x.dtype not in (torch.float32, torch.float16) or not x.is_cuda or not x.is_contiguous():
+            raise ValueError("x must be a contiguous float32 or float16 device tensor")
+        _dev_check(q, torch.uint8, "q")
+        if q.numel() != x.numel():
+            raise ValueError("q and x differ in size")
+        self._chk(self.lib.emc2_quantize_e4m3(self.h, F32 if x.dtype == torch.float32 else F16, _ptr(x), x.numel(),
+                                              inv_scale, _ptr(q), _stream()))
+
+    def spconv_e4m3(self, x: torch.Tensor, w_packed: torch.Tensor, cin: int, cout: int, mul: torch.Tensor, add: torch.Tensor,
+                    relu: bool, nbr: torch.Tensor, n_out: torch.Tensor, capacity_out: int, out: torch.Tensor,
+                    n_in_rows: Optional[int] = None) -> None:
+        """E4M3 conv: x [n][Cin] uint8 codes, weights packed by pack_weights_i8 (as bytes), out float32 or float16."""
+        _dev_check(x, torch.uint8, "x")
+        _dev_check(mul, torch.float32, "mul")
+        _dev_check(add, torch.float32, "add")
+        _dev_check(nbr, torch.int32, "nbr")
+        _dev_check(n_out, torch.int32, "n_out")
+        if w_packed.dtype not in (torch.uint8, torch.int8) or not w_packed.is_cuda or not w_packed.is_contiguous():
+            raise ValueError("w_packed must be a contiguous 8-bit device tensor")
+        if out.dtype not in (torch.float32, torch.float16) or not out.is_cuda or not out.is_contiguous():
+            raise ValueError("out must be a contiguous float32 or float16 device tensor")
+        if x.dim() != 2 or x.shape[1] != cin or w_packed.numel() != 27 * cin * cout or mul.numel() != cout or add.numel() != cout:
+            raise ValueError("shape mismatch")
+        if out.numel() < capacity_out * cout or nbr.numel() < 27 * capacity_out:
+            raise ValueError("out / nbr smaller than capacity_out")
+        self._chk(self.lib.emc2_spconv_e4m3(self.h, _ptr(x), _ptr(w_packed), _ptr(mul), _ptr(add), int(bool(relu)),
+                                            F32 if out.dtype == torch.float32 else F16, _ptr(nbr), _ptr(n_out), capacity_out,
+                                            int(x.shape[0]) if n_in_rows is None else n_in_rows, cin, cout, _ptr(out), _stream()))
 
     def uses_mfma(self, dtype: int, cin: int, cout: int) -> bool:
         return bool(self.lib.emc2_spconv_uses_mfma(dtype, cin, cout))

@@ -18,6 +18,7 @@
 namespace {
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -30,6 +31,33 @@ __device__ __forceinline__ int quant_i8(float v, float inv_scale) {
   r = r > 127.f ? 127.f : r;
   r = r < -127.f ? -127.f : r;
   return (int)r;
+}
+
+// E4M3 (bias 7, no infinities, largest value 448): nearest finite value of t, ties to the even code, saturating,
+// NaN -> 0, a result of zero always +0.  Integer arithmetic on the fp32 bits, so that no conversion mode of the
+// hardware enters: above the subnormal range the 20 low mantissa bits are rounded away (the carry runs into the
+// exponent by itself); below 2^-6 the value is a multiple of 2^-9.
+__device__ __forceinline__ uint32_t quant_e4m3(float t) {
+  if (!(t == t)) return 0u;
+  const float a = fabsf(t);
+  uint32_t code;
+  if (a >= 448.0f) {
+    code = 0x7Eu;
+  } else if (a < 0.015625f) {
+    code = (uint32_t)rintf(a * 512.0f);          // exact product; ties to even; 8 is the first normal code
+  } else {
+    const uint32_t bits = __float_as_uint(a);
+    const uint32_t r = (bits + 0x7FFFFu + ((bits >> 20) & 1u)) >> 20;   // (exponent << 3 | mantissa), rounded to nearest even
+    code = r - (120u << 3);
+    code = code > 0x7Eu ? 0x7Eu : code;          // 464 .. 448 rounds up to a code that is not a number: saturate
+  }
+  return (code != 0u && t < 0.0f) ? (code | 0x80u) : code;
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256) k_quantize_e4m3(const T* __restrict__ x, int64_t n, float inv_scale, uint8_t* __restrict__ q) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) q[i] = (uint8_t)quant_e4m3((float)x[i] * inv_scale);
 }
 
 template <typename T>
@@ -64,11 +92,17 @@ __global__ void __launch_bounds__(256) k_pack_weights_i8(const int8_t* __restric
   packed[p] = make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// OUTQ: 1 = int8 output (re-quantised), 0 = fp16 output.
+// F8: 0 = int8 operands, exact int32 accumulation (v_mfma_i32_16x16x64_i8); 1 = E4M3 operands, fp32 accumulation
+//     (two v_mfma_f32_16x16x32_fp8_fp8 per 16-byte operand: its low and its high 8 bytes; features and packed weights
+//     split the same way, so the contraction pairs the same channels).
+// OUTQ: int8 operands: 1 = int8 output (re-quantised), 0 = fp16 output; E4M3 operands: 1 = fp32 output, 0 = fp16 output.
 // waves per SIMD the register allocator must leave room for: three where the operands in flight are few
 template <int CIN, int COUT> struct QCfg { static constexpr int MINW = (CIN == 64 && COUT == 32) ? 3 : 2; };
 
-template <int CIN, int COUT, int OUTQ>
+template <int F8> struct QAcc { typedef intx4 type; };
+template <> struct QAcc<1> { typedef floatx4 type; };
+
+template <int CIN, int COUT, int OUTQ, int F8>
 __global__ void __launch_bounds__(kQThreads, (QCfg<CIN, COUT>::MINW))
 k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const float* __restrict__ mul,
             const float* __restrict__ add, int relu, float inv_out_scale, const int32_t* __restrict__ nbr,
@@ -83,7 +117,7 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
   static_assert((W16 & (W16 - 1)) == 0, "piece count is a power of two");
   constexpr int WMASK = W16 - 1;              // surplus threads copy redundantly rather than under a branch
   constexpr int NA = MT * KS;                 // A-operand loads per tap
-  constexpr int ES = OUTQ ? 1 : 2;            // bytes per output element
+  constexpr int ES = F8 ? (OUTQ ? 4 : 2) : (OUTQ ? 1 : 2);   // bytes per output element
   constexpr int OCH = COUT * ES / 16;         // 16-byte pieces per output row
   constexpr int OPITCH = (OCH + 1) * 16;      // epilogue tile row pitch in bytes
   __shared__ u32x4 wl[2][W16];
@@ -109,11 +143,12 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
   const int32_t dead = live ? 0 : -1;   // OR-ed into kernel-map entries: rows past n_out have no neighbours
   unsigned long long oob = 0ull;        // lanes that saw an entry outside [0, n_in)
 
-  intx4 acc[MT][NT];
+  typedef typename QAcc<F8>::type acc_t;
+  acc_t acc[MT][NT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int j = 0; j < NT; ++j) acc[mt][j] = intx4{0, 0, 0, 0};
+    for (int j = 0; j < NT; ++j) acc[mt][j] = acc_t{0, 0, 0, 0};
 
   int32_t jq[3][3];         // kernel-map entries of groups g, g+1, g+2 (as loaded; masked where used)
   u32x4 areg[3][NA];        // A operands in flight; tap x lives in set x % 3
@@ -179,9 +214,18 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-          for (int j = 0; j < NT; ++j)
-            acc[mt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(intx4, areg[kx][mt * KS + ks]),
-                                                               __builtin_bit_cast(intx4, b[j]), acc[mt][j], 0, 0, 0);
+          for (int j = 0; j < NT; ++j) {
+            if constexpr (F8) {
+              const u32x4 av = areg[kx][mt * KS + ks], bv = b[j];
+              const long a_lo = (long)(((unsigned long)av.y << 32) | av.x), a_hi = (long)(((unsigned long)av.w << 32) | av.z);
+              const long b_lo = (long)(((unsigned long)bv.y << 32) | bv.x), b_hi = (long)(((unsigned long)bv.w << 32) | bv.z);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_lo, b_lo, acc[mt][j], 0, 0, 0);
+              acc[mt][j] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a_hi, b_hi, acc[mt][j], 0, 0, 0);
+            } else {
+              acc[mt][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(intx4, areg[kx][mt * KS + ks]),
+                                                                 __builtin_bit_cast(intx4, b[j]), acc[mt][j], 0, 0, 0);
+            }
+          }
       }
       // the freed register set takes the A operands of tap + 3 (entries of "group 9" do not exist)
       const int32_t past = g < 8 ? 0 : -1;
@@ -227,7 +271,8 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
         v = v + ad[j];
         if (relu) v = v > 0.f ? v : 0.f;
         uint8_t* dst = otile + (4 * q + e) * OPITCH + (16 * j + m) * ES;
-        if (OUTQ) *reinterpret_cast<int8_t*>(dst) = (int8_t)quant_i8(v, inv_out_scale);
+        if (F8 && OUTQ) *reinterpret_cast<float*>(dst) = v;
+        else if (OUTQ) *reinterpret_cast<int8_t*>(dst) = (int8_t)quant_i8(v, inv_out_scale);
         else *reinterpret_cast<uint16_t*>(dst) = __half_as_ushort(__float2half_rn(v));
       }
     }
@@ -245,12 +290,12 @@ k_spconv_i8(const int8_t* __restrict__ in, const u32x4* __restrict__ wp, const f
   }
 }
 
-template <int CIN, int COUT, int OUTQ>
+template <int CIN, int COUT, int OUTQ, int F8 = 0>
 void launch_i8(const void* d_in, const void* d_wp, const float* d_mul, const float* d_add, int relu, float inv_out_scale,
                const int32_t* d_nbr, const int32_t* d_n_out, int64_t capacity_out, int32_t n_in, int32_t* dev_flags,
                const void* d_zero_row, void* d_out, hipStream_t s) {
   const int64_t rows_per_block = kQWaves * 64;
-  hipLaunchKernelGGL((k_spconv_i8<CIN, COUT, OUTQ>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),
+  hipLaunchKernelGGL((k_spconv_i8<CIN, COUT, OUTQ, F8>), dim3((unsigned)(emc2_div_up(capacity_out, rows_per_block) + 8)),
                      dim3(kQThreads), 0, s, (const int8_t*)d_in, (const u32x4*)d_wp, d_mul, d_add, relu, inv_out_scale, d_nbr,
                      d_n_out, capacity_out, n_in, dev_flags, (const int8_t*)d_zero_row, d_out);
 }
@@ -319,4 +364,53 @@ extern "C" emc2_status emc2_spconv_i8(emc2_ctx* ctx, const int8_t* d_in, const v
   CASE(64, 32) CASE(64, 64) CASE(128, 32) CASE(128, 64)
 #undef CASE
   return emc2_check_hip(ctx, hipGetLastError(), "emc2_spconv_i8 launch");
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// E4M3 variant: same kernel, same packed-weight byte order (emc2_pack_weights_i8 permutes bytes, whatever they encode)
+// ---------------------------------------------------------------------------------------------------------
+extern "C" emc2_status emc2_quantize_e4m3(emc2_ctx* ctx, emc2_dtype dtype, const void* d_x, int64_t n, float inv_scale,
+                                          uint8_t* d_q, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (n < 0 || (n > 0 && (!d_x || !d_q))) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_quantize_e4m3: bad argument");
+  if (!(inv_scale == inv_scale)) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_quantize_e4m3: inv_scale is not a number");
+  if (n == 0) return EMC2_OK;
+  const dim3 grid((unsigned)emc2_div_up(n, 256)), blk(256);
+  hipStream_t s = (hipStream_t)stream;
+  if (dtype == EMC2_F32) hipLaunchKernelGGL(k_quantize_e4m3<float>, grid, blk, 0, s, (const float*)d_x, n, inv_scale, d_q);
+  else if (dtype == EMC2_F16) hipLaunchKernelGGL(k_quantize_e4m3<__half>, grid, blk, 0, s, (const __half*)d_x, n, inv_scale, d_q);
+  else return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_quantize_e4m3: input must be F32 or F16");
+  return emc2_check_hip(ctx, hipGetLastError(), "emc2_quantize_e4m3 launch");
+}
+
+extern "C" emc2_status emc2_spconv_e4m3(emc2_ctx* ctx, const uint8_t* d_in, const void* d_w_packed, const float* d_mul,
+                                        const float* d_add, int32_t relu, emc2_dtype out_dtype, const int32_t* d_nbr,
+                                        const int32_t* d_n_out, int64_t capacity_out, int64_t n_in_rows, int32_t cin,
+                                        int32_t cout, void* d_out, void* stream) {
+  if (!ctx) return EMC2_ERR_INVALID_ARG;
+  if (!d_in || !d_w_packed || !d_mul || !d_add || !d_nbr || !d_n_out || !d_out)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_e4m3: null argument");
+  if (capacity_out < 1) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_e4m3: capacity_out < 1");
+  if (n_in_rows < 0) return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_e4m3: n_in_rows < 0");
+  if (((uintptr_t)d_in | (uintptr_t)d_w_packed | (uintptr_t)d_out) & 15u)
+    return emc2_fail(ctx, EMC2_ERR_INVALID_ARG, "emc2_spconv_e4m3: d_in, d_w_packed and d_out must be 16-byte aligned");
+  if (!i8_shape_ok(cin, cout))
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv_e4m3: Cin must be 64 or 128 and Cout 32 or 64");
+  if (out_dtype != EMC2_F32 && out_dtype != EMC2_F16)
+    return emc2_fail(ctx, EMC2_ERR_UNSUPPORTED, "emc2_spconv_e4m3: output must be F32 or F16");
+  const int32_t n_in = n_in_rows > 0x7fffffff ? 0x7fffffff : (int32_t)n_in_rows;
+  hipStream_t s = (hipStream_t)stream;
+  const int rl = relu ? 1 : 0;
+#define CASE(CI, CO)                                                                                                         \
+  if (cin == CI && cout == CO) {                                                                                             \
+    if (out_dtype == EMC2_F32)                                                                                               \
+      launch_i8<CI, CO, 1, 1>(d_in, d_w_packed, d_mul, d_add, rl, 0.f, d_nbr, d_n_out, capacity_out, n_in, ctx->dev_words,   \
+                              ctx->zero_row, d_out, s);                                                                      \
+    else                                                                                                                     \
+      launch_i8<CI, CO, 0, 1>(d_in, d_w_packed, d_mul, d_add, rl, 0.f, d_nbr, d_n_out, capacity_out, n_in, ctx->dev_words,   \
+                              ctx->zero_row, d_out, s);                                                                      \
+  }
+  CASE(64, 32) CASE(64, 64) CASE(128, 32) CASE(128, 64)
+#undef CASE
+  return emc2_check_hip(ctx, hipGetLastError(), "emc2_spconv_e4m3 launch");
 }
