@@ -125,6 +125,8 @@ def measure_probes(torch):
     lib.emc2_probe_empty.argtypes = [ctypes.c_int32, vp]
     lib.emc2_probe_copy.argtypes = [vp, vp, ctypes.c_int64, vp]
     lib.emc2_probe_mfma_f16.argtypes = [ctypes.c_int64, ctypes.c_int32, vp, vp]
+    lib.emc2_probe_fill.argtypes = [vp, ctypes.c_int64, vp]
+    lib.emc2_probe_atomic.argtypes = [vp, ctypes.c_int32, ctypes.c_int64, vp]
     out = {}
     s = torch.cuda.Stream()
     with torch.cuda.stream(s):
@@ -158,6 +160,12 @@ def measure_probes(torch):
         ms = timed_loop(torch, lambda: lib.emc2_probe_copy(vp(dst.data_ptr()), vp(src.data_ptr()), nbytes, sp), reps=10)
         out["copy_GBs"] = 2.0 * nbytes / (ms * 1e-3) / 1e9
         out["copy_frac_of_hbm_peak"] = out["copy_GBs"] / PEAK_HBM_GBS
+        ms = timed_loop(torch, lambda: lib.emc2_probe_fill(vp(dst.data_ptr()), nbytes, sp), reps=10)
+        out["fill_GBs"] = nbytes / (ms * 1e-3) / 1e9
+        # scattered atomics: 4 M of them on a 64 MiB table (the rate does not depend on the table's size)
+        n_at = 4 << 20
+        ms = timed_loop(torch, lambda: lib.emc2_probe_atomic(vp(dst.data_ptr()), 24, n_at, sp), reps=10)
+        out["random_atomics_G_per_s"] = n_at / (ms * 1e-3) / 1e9
         del src, dst
         # dense MFMA loop: 2 blocks of 4 waves per CU (2 waves per SIMD)
         blocks, iters = 512, 20000
@@ -246,14 +254,21 @@ def measure_config(cfg_index, args, steps, warmup, full):
 
     # flop / byte accounting from the kernel maps of this batch (outside the timed region)
     layers = []                      # (branch index, layer index, Layer, pairs, flops)
+    layer_bytes = {}                 # ideal-reuse HBM bytes of a layer: features in and out, kernel map, weights
     vox = []
     for bi, (ctx, br) in enumerate(runner.branches):
         vox.append([int(lv.n.item()) for lv in br.levels])
+        lvl = 0
         for li, layer in enumerate(br.branch.layers):
             nbr, lv = br.layer_map(li)
             n = int(lv.n.item())
+            n_in_rows = vox[bi][lvl]
+            if layer.kind == STRIDED:
+                lvl += 1
             pairs = int((nbr[:, :n] >= 0).sum().item())
             layers.append((bi, li, layer, pairs, 2.0 * pairs * layer.cin * layer.cout))
+            esz = 4 if cfg.dtype == 0 else 2
+            layer_bytes[(bi, li)] = n_in_rows * layer.cin * esz + n * layer.cout * esz + 27.0 * n * 4 + 27.0 * layer.cin * layer.cout * esz
     total_flops = sum(l[4] for l in layers)
     ctx0 = runner.branches[0][0]
 
@@ -357,22 +372,30 @@ def measure_config(cfg_index, args, steps, warmup, full):
                                      "launches_timed": shared_n,
                                      "note": f"bracketed inside the timed steps, {depth} batches in flight"}
 
-    # memory-bound stages against the HBM peak: algorithmic bytes over the calibration pass's stage time.
-    # voxelize: 16 B (+ 4 B batch id) per point read, 36 B per voxel written; kernel maps: 16 B of coordinates read
-    # and 27 x 4 B of map written per output (+ 16 B of coordinates written per stride-2 output, 16 B per input read)
+    # memory-bound stages against the HBM peak: bytes over the calibration pass's stage time, counted two ways.
+    # "algorithmic": what this design must move at the least -- voxelize: 16 B (+ 4 B batch id) per point read, 36 B
+    # per voxel written; kernel maps: 16 B of coordinates read and 27 x 4 B of map written per output (+ 16 B of
+    # coordinates written per stride-2 output, 16 B per input read); the index words are shared by 32 cells.
+    # "per_unit_of_the_method": the per-unit figures of a hash-based formulation of the same steps -- 44 B per point
+    # (16 read, a key slot, five accumulator updates) + 36 B per voxel; 340 B per submanifold output (coordinates, 27
+    # probes of 8 B, 27 entries); 360 B per stride-2 output + 80 B per input.
     per_pt = 16.0 + (4.0 if batch is not None else 0.0)
     stage_bytes = {"voxelize": 0.0, "kmap_subm": 0.0, "kmap_strided": 0.0}
+    unit_bytes = {"voxelize": 0.0, "kmap_subm": 0.0, "kmap_strided": 0.0}
     for bi, (_, br) in enumerate(runner.branches):
         nv = vox[bi]
         stage_bytes["voxelize"] += n_points * per_pt + nv[0] * 36.0
+        unit_bytes["voxelize"] += n_points * 44.0 + nv[0] * 36.0
         lvl, seen = 0, set()
         for layer in br.branch.layers:
             if layer.kind == STRIDED:
                 stage_bytes["kmap_strided"] += nv[lvl] * 16.0 + nv[lvl + 1] * (16.0 + 16.0 + 108.0)
+                unit_bytes["kmap_strided"] += nv[lvl] * 80.0 + nv[lvl + 1] * 360.0
                 lvl += 1
             elif lvl not in seen:
                 seen.add(lvl)
                 stage_bytes["kmap_subm"] += nv[lvl] * (16.0 + 108.0)
+                unit_bytes["kmap_subm"] += nv[lvl] * 340.0
     if cfg.camera is not None:
         stage_bytes["project_gather"] = n_points * (16.0 + 5 * 2.0 * cfg.camera.channels + 1.0)
     stage_hbm = {}
@@ -380,6 +403,9 @@ def measure_config(cfg_index, args, steps, warmup, full):
         if stage_ms.get(k_) and b_ > 0:
             gbs = b_ / (stage_ms[k_] * 1e-3) / 1e9
             stage_hbm[k_] = {"algorithmic_MB": b_ / 1e6, "ms": stage_ms[k_], "GB/s": gbs, "frac_of_hbm_peak": gbs / PEAK_HBM_GBS}
+            if unit_bytes.get(k_):
+                stage_hbm[k_]["per_unit_of_the_method_MB"] = unit_bytes[k_] / 1e6
+                stage_hbm[k_]["per_unit_frac_of_hbm_peak"] = unit_bytes[k_] / (stage_ms[k_] * 1e-3) / 1e9 / PEAK_HBM_GBS
 
     res = {
         "config": cfg.index, "name": cfg.name,
@@ -400,7 +426,10 @@ def measure_config(cfg_index, args, steps, warmup, full):
         "conv_layers": [{"branch": runner.branches[bi][1].branch.name, "cin": l.cin, "cout": l.cout, "strided": l.kind == STRIDED,
                          "pairs": p, "ms": conv_ms.get((bi, li), 0.0), "kernel": ctx0.spconv_kernel(cfg.dtype, l.cin, l.cout, l.kind),
                          "frac_of_mfma_peak": (f / (conv_ms[(bi, li)] * 1e-3) / 1e12 / PEAK_MFMA_F16_TFLOPS)
-                         if conv_ms.get((bi, li)) and ctx0.uses_mfma(cfg.dtype, l.cin, l.cout) else None}
+                         if conv_ms.get((bi, li)) and ctx0.uses_mfma(cfg.dtype, l.cin, l.cout) else None,
+                         "ideal_reuse_MB": layer_bytes[(bi, li)] / 1e6,
+                         "frac_of_hbm_peak": (layer_bytes[(bi, li)] / (conv_ms[(bi, li)] * 1e-3) / 1e9 / PEAK_HBM_GBS)
+                         if conv_ms.get((bi, li)) else None}
                         for bi, li, l, p, f in layers],
     }
 
@@ -552,6 +581,31 @@ def side_decoder(torch):
         ops = 2.0 * pairs * 64 * 64
         quant.append({"cin": 64, "cout": 64, "strided": layer.kind == STRIDED, "pairs": pairs, "ms_int8": ms_q, "ms_fp16_same_map": ms_h,
                       "useful_TOPS": ops / (ms_q * 1e-3) / 1e12, "frac_of_int8_peak": ops / (ms_q * 1e-3) / 1e12 / 5000.0})
+    # Cross-layer fusion of the two submanifold layers of a stage (paper Sec. 3.6, graph optimisation (3)): a block
+    # that owns T consecutive output rows of the second layer needs the first layer's outputs on every row its map
+    # names (the halo H), so a fused block recomputes |H| / |T| times the first layer's work.  Measured on this
+    # frame's maps for the block size the conv kernels use (512 rows) and for a whole 4096-row super-block.
+    halo = []
+    lvl = 0
+    for li, layer in enumerate(runner.branch.layers):
+        if layer.kind == STRIDED:
+            lvl += 1
+            continue
+        lv_o = runner.levels[lvl]
+        if lv_o.subm_nbr is None or any(h["level"] == lvl for h in halo):
+            continue
+        n_o = int(lv_o.n.item())
+        row = {"level": lvl, "voxels": n_o}
+        for tile in (512, 4096):
+            n_t = n_o // tile
+            if n_t == 0:
+                continue
+            m = lv_o.subm_nbr[:, :n_t * tile].reshape(27, n_t, tile).permute(1, 0, 2).reshape(n_t, 27 * tile)
+            srt, _ = torch.sort(m, dim=1)
+            distinct = ((srt[:, 1:] != srt[:, :-1]) & (srt[:, 1:] >= 0)).sum(dim=1) + (srt[:, 0] >= 0).to(torch.int64)
+            row[f"rows_needed_per_row_owned_tile{tile}"] = float(distinct.double().mean().item()) / tile
+        halo.append(row)
+    out["two_layer_fusion_halo"] = halo
     cr.close()
     return out, quant
 

@@ -22,6 +22,24 @@ __global__ void __launch_bounds__(256) k_probe_copy(uint4* __restrict__ dst, con
   for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+__global__ void __launch_bounds__(256) k_probe_fill(uint4* __restrict__ dst, int64_t n16) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(1u, 2u, 3u, 4u);
+}
+
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+  x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+  return x;
+}
+
+// one atomic OR per thread on a pseudo-random 4-byte word of a table of 2^log2_words words
+__global__ void __launch_bounds__(256) k_probe_atomic(uint32_t* __restrict__ table, int log2_words, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint32_t h = probe_hash((uint32_t)i);
+  atomicOr(table + (h & ((1u << log2_words) - 1u)), 1u << (h >> 27));
+}
+
 __global__ void __launch_bounds__(256) k_probe_mfma_f16(int64_t iters, float* __restrict__ sink) {
   // operands that the compiler cannot fold: they depend on the thread index
   half8 a, b;
@@ -61,6 +79,23 @@ extern "C" int32_t emc2_probe_copy(void* dst, const void* src, int64_t bytes, vo
   int64_t blocks = (n16 + 255) / 256;
   if (blocks > 256 * 16) blocks = 256 * 16;   // 16 blocks per CU, the rest by grid stride
   hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, (const uint4*)src, n16);
+  return (int32_t)hipGetLastError();
+}
+
+extern "C" int32_t emc2_probe_fill(void* dst, int64_t bytes, void* stream) {
+  if (!dst || bytes < 0 || (bytes & 15) || ((uintptr_t)dst & 15)) return (int32_t)hipErrorInvalidValue;
+  if (bytes == 0) return 0;
+  const int64_t n16 = bytes / 16;
+  int64_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(k_probe_fill, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, n16);
+  return (int32_t)hipGetLastError();
+}
+
+extern "C" int32_t emc2_probe_atomic(uint32_t* d_table, int32_t log2_words, int64_t n, void* stream) {
+  if (!d_table || log2_words < 0 || log2_words > 31 || n < 0) return (int32_t)hipErrorInvalidValue;
+  if (n == 0) return 0;
+  hipLaunchKernelGGL(k_probe_atomic, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, d_table, log2_words, n);
   return (int32_t)hipGetLastError();
 }
 
