@@ -346,7 +346,10 @@ extern "C" int32_t emc2_spconv_uses_mfma(emc2_dtype dtype, int32_t cin, int32_t 
   return (dtype == EMC2_F16 || dtype == EMC2_BF16) && emc2_spconv_mfma_supported(cin, cout) ? 1 : 0;
 }
 
+// shapes of the thread-per-row vector-ALU kernel (fp32) and of the small-channel matrix-core kernel (16-bit); 16 -> 32
+// was tried on the latter and is three times slower there than on the staged MFMA kernel
 static bool small_covers(int cin, int cout) { return (cin == 4 && (cout == 16 || cout == 32)) || (cin == 16 && cout == 16); }
+static bool rows_covers(int cin, int cout) { return small_covers(cin, cout); }
 
 extern "C" const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t cout, int32_t map_hint) {
   if (dtype != EMC2_F32 && dtype != EMC2_F16 && dtype != EMC2_BF16) return nullptr;
@@ -354,8 +357,8 @@ extern "C" const char* emc2_spconv_kernel(emc2_dtype dtype, int32_t cin, int32_t
     if (!emc2_spconv_direct_supported(cin, cout)) return "k_spconv_mfma";
     return (map_hint == EMC2_CONV_SUBM && emc2_spconv_span_supported(cin, cout)) ? "k_spconv_span" : "k_spconv_direct";
   }
-  if (!small_covers(cin, cout)) return "k_spconv_alu";
-  return dtype == EMC2_F32 ? "k_spconv_small" : "k_spconv_rows";
+  if (dtype == EMC2_F32) return small_covers(cin, cout) ? "k_spconv_small" : "k_spconv_alu";
+  return rows_covers(cin, cout) ? "k_spconv_rows" : "k_spconv_alu";
 }
 
 extern "C" emc2_status emc2_pack_weights(emc2_ctx* ctx, emc2_dtype dtype, const void* d_w, int32_t cin, int32_t cout,

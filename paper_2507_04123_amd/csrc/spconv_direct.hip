@@ -14,12 +14,13 @@
 //   Absent neighbours read a zeroed row instead (an address select, no masking of data).
 //
 // LDS holds only the weights of the current and the next tap (packed in B-fragment order, copied once
-// per block and tap, requested three taps ahead) and a small tile for the epilogue's transposition.  Per tap and wave: 8 LDS reads
-// for 32 matrix instructions at Cin = Cout = 64 (the staged kernel: 16 reads and 8 writes for 16).
+// per block and tap, requested three taps ahead) and a small tile for the epilogue's transposition.
 //
-// A block is 4 waves; a wave owns 64 consecutive output rows (4 tiles of 16) and all Cout columns, so the
-// fp32 accumulators never leave registers.  Gathers run 3 taps ahead of their use; kernel-map entries two
-// (dz,dy) groups ahead.  Every load is unconditional so the compiler can count the loads in flight.
+// A block is 4 waves; a wave owns 32 consecutive output rows (2 tiles of 16; 64 rows = 4 tiles at 32 -> 32, where
+// the accumulators are few) and all Cout columns, so the fp32 accumulators never leave registers.  Gathers run 3
+// taps ahead of their use; kernel-map entries two (dz,dy) groups ahead.  Every load is unconditional so the
+// compiler can count the loads in flight.  Shapes: Cin, Cout in {32, 64}, and 64 -> 128 / 128 -> 128, where a
+// tap's matrix work per gathered byte doubles and the kernel leaves the staged per-tap kernel behind by a third.
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
@@ -78,8 +79,9 @@ template <int CIN, int COUT> struct DirectCfg {
   // 16-row tiles per wave (2 or 4): fewer rows per wave mean fewer accumulators and operands in flight, so more
   // waves fit a SIMD and cover each other's stalls; more rows per wave reuse a weight fragment read more often
   static constexpr int MT = (CIN <= 32 && COUT <= 32) ? 4 : 2;
-  // waves per SIMD the register allocator must leave room for
-  static constexpr int MINW = 3;
+  // waves per SIMD the register allocator must leave room for (the 128-channel shapes keep 64-128 accumulators
+  // and as many operands in flight)
+  static constexpr int MINW = (CIN >= 128 || COUT >= 128) ? 2 : 3;
 };
 
 template <int DT, int CIN, int COUT>
@@ -275,7 +277,7 @@ void launch_direct(const void* d_in, const void* d_wp, const float* d_scale, con
 }  // namespace
 
 bool emc2_spconv_direct_supported(int cin, int cout) {
-  return (cin == 32 || cin == 64) && (cout == 32 || cout == 64);
+  return ((cin == 32 || cin == 64) && (cout == 32 || cout == 64)) || (cin == 128 && cout == 128) || (cin == 64 && cout == 128);
 }
 
 void emc2_spconv_direct_pack(const void* d_w, int cin, int cout, void* d_packed, hipStream_t stream) {
@@ -296,5 +298,6 @@ void emc2_spconv_direct_launch(emc2_dtype dtype, const void* d_in, const void* d
   }
   CASE(EMC2_F16, 32, 32) CASE(EMC2_F16, 32, 64) CASE(EMC2_F16, 64, 32) CASE(EMC2_F16, 64, 64)
   CASE(EMC2_BF16, 32, 32) CASE(EMC2_BF16, 32, 64) CASE(EMC2_BF16, 64, 32) CASE(EMC2_BF16, 64, 64)
+  CASE(EMC2_F16, 128, 128) CASE(EMC2_F16, 64, 128) CASE(EMC2_BF16, 128, 128) CASE(EMC2_BF16, 64, 128)
 #undef CASE
 }
