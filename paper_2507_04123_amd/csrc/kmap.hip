@@ -159,7 +159,8 @@ __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ out_coor
           if ((cw.x >> bit) & 1u) j = (int32_t)(cw.y + __popc(cw.x & ((1u << bit) - 1u)));
         }
         if (j >= n_in) j = -1;  // only after a capacity overflow upstream
-        nbr[(int64_t)((kz * 3 + ky) * 3 + kx) * capacity_out + o] = j;
+        // written once, read by a later kernel: a streaming store keeps the map from displacing the index in the caches
+        __builtin_nontemporal_store(j, &nbr[(int64_t)((kz * 3 + ky) * 3 + kx) * capacity_out + o]);
       }
     }
   }
