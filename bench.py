@@ -578,9 +578,20 @@ def side_decoder(torch):
         p = runner.params[li]
         ms_h = timed_loop(torch, lambda: ctx.spconv(cfg.dtype, x16, runner.wdev[li][0], p["scale"], p["shift"], 2, nbr_t, lv_o.n, lv_o.cap,
                                                     runner.acts[li], w_layout=runner.wdev[li][1], map_hint=layer.kind))
+        # the same layer in 8-bit floating point (E4M3 codes, fp32 accumulation on the fp8 matrix cores)
+        x8 = torch.empty((max(n_in, 1), 64), dtype=torch.uint8, device="cuda")
+        ctx.quantize_e4m3(torch.randn((max(n_in, 1), 64), device="cuda"), 1.0, x8)
+        w8 = torch.empty((27, 64, 64), dtype=torch.uint8, device="cuda")
+        ctx.quantize_e4m3(torch.randn((27, 64, 64), device="cuda").mul_(0.1), 8.0, w8)
+        w8p = torch.empty((27 * 64 * 64,), dtype=torch.int8, device="cuda")
+        ctx.pack_weights_i8(w8.view(torch.int8), w8p)
+        y8 = torch.empty((lv_o.cap, 64), dtype=torch.float16, device="cuda")
+        ms_8 = timed_loop(torch, lambda: ctx.spconv_e4m3(x8, w8p, 64, 64, ml, ad, True, nbr_t, lv_o.n, lv_o.cap, y8))
         ops = 2.0 * pairs * 64 * 64
-        quant.append({"cin": 64, "cout": 64, "strided": layer.kind == STRIDED, "pairs": pairs, "ms_int8": ms_q, "ms_fp16_same_map": ms_h,
-                      "useful_TOPS": ops / (ms_q * 1e-3) / 1e12, "frac_of_int8_peak": ops / (ms_q * 1e-3) / 1e12 / 5000.0})
+        quant.append({"cin": 64, "cout": 64, "strided": layer.kind == STRIDED, "pairs": pairs, "ms_int8": ms_q, "ms_e4m3": ms_8,
+                      "ms_fp16_same_map": ms_h,
+                      "useful_TOPS": ops / (ms_q * 1e-3) / 1e12, "frac_of_int8_peak": ops / (ms_q * 1e-3) / 1e12 / 5000.0,
+                      "e4m3_useful_TFLOPs": ops / (ms_8 * 1e-3) / 1e12, "frac_of_fp8_peak": ops / (ms_8 * 1e-3) / 1e12 / 5000.0})
     # Cross-layer fusion of the two submanifold layers of a stage (paper Sec. 3.6, graph optimisation (3)): a block
     # that owns T consecutive output rows of the second layer needs the first layer's outputs on every row its map
     # names (the halo H), so a fused block recomputes |H| / |T| times the first layer's work.  Measured on this
@@ -679,6 +690,21 @@ def side_dispatcher(torch):
         out.append({"scenes": n_sc, "proposals": len(pr_np), "ms": ms_d, "scenes_per_expert": cn.tolist(),
                     "algorithmic_MB": db / 1e6, "GB/s": db / (ms_d * 1e-3) / 1e9})
     ctx.close()
+    # scene-level routing end to end: dispatch -> group the points by expert -> every expert's stack on its group
+    from paper_2507_04123_amd.configs import expert_branches, get_config
+    from paper_2507_04123_amd.pipeline import RoutedRunner
+    cfg5 = get_config(5)
+    pts_np, batch_np = gen.make_frames(cfg5)
+    n_sc = cfg5.n_frames
+    rr = RoutedRunner(expert_branches(n_sc), cfg5.dtype, len(pts_np), n_sc, seed=7)
+    pr_np, sc_np = gen.make_proposals(n_sc, gen.frame_seed(5, 0))
+    pts, scene = torch.from_numpy(pts_np).cuda(), torch.from_numpy(batch_np).cuda()
+    pr, sc_t = torch.from_numpy(pr_np).cuda(), torch.from_numpy(sc_np).cuda()
+    ms_r = timed_loop(torch, lambda: rr.run(pts, scene, pr, sc_t, 23.5, 0.5), reps=10)
+    rr.status_sync()
+    out.append({"routed_run": f"{n_sc} scenes of config 5's cloud through dispatch, grouping and the three expert stacks (one stream)",
+                "ms": ms_r, "scenes_per_expert": rr.counts.tolist(), "frames/s": n_sc / (ms_r * 1e-3)})
+    rr.close()
     return out
 
 

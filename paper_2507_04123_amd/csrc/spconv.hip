@@ -219,21 +219,19 @@ __global__ void __launch_bounds__(256) k_spconv_rows(const uint16_t* __restrict_
     for (int g = 0; g < G; ++g) acc[r][g] = float4_t{0.f, 0.f, 0.f, 0.f};
   __syncthreads();   // weights in LDS
   const int jq = lane & 3;
-  // all kernel-map entries of the wave's rows are requested at once, before the first of them is used
-  int32_t jall[RG][27];
-#pragma unroll
-  for (int r = 0; r < RG; ++r)
-#pragma unroll
-    for (int k = 0; k < 27; ++k) jall[r][k] = nrow[r][(int64_t)k * capacity_out];
-#pragma unroll
+#pragma unroll 1
   for (int k0 = 0; k0 < 27; k0 += TB) {
     int32_t j[RG][TB];
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+#pragma unroll
+      for (int t = 0; t < TB; ++t) j[r][t] = nrow[r][(int64_t)(k0 + t) * capacity_out];
     uint32_t x[RG][TB][RW];
 #pragma unroll
     for (int r = 0; r < RG; ++r)
 #pragma unroll
       for (int t = 0; t < TB; ++t) {
-        j[r][t] = emc2_entry(jall[r][k0 + t], dead[r], n_in, oob);
+        j[r][t] = emc2_entry(j[r][t], dead[r], n_in, oob);
         const char* src = reinterpret_cast<const char*>(in + (int64_t)(j[r][t] >= 0 ? j[r][t] : 0) * CIN);
         if constexpr (RW == 2) {
           const u32x2_t v = *reinterpret_cast<const u32x2_t*>(src);
