@@ -225,6 +225,19 @@ def cpu_baseline(cfg, pts_np, batch_np, threads, single_thread_sample=True):
 # one configuration: throughput, calibration, roofline of its dominant kernel
 # ----------------------------------------------------------------------------------------------------------
 
+_REPLAY_STREAMS = []
+
+
+def replay_stream(torch, k):
+    """The k-th of the streams the batches in flight are replayed on: created once, first, and shared by every
+    configuration measured in this process.  The runtime spreads streams over a handful of hardware queues as they
+    appear; two replay streams that land on one queue serialise their batches, which a later configuration's fresh
+    streams did more often than the first one's."""
+    while len(_REPLAY_STREAMS) <= k:
+        _REPLAY_STREAMS.append(torch.cuda.Stream())
+    return _REPLAY_STREAMS[k]
+
+
 def measure_config(cfg_index, args, steps, warmup, full):
     """`full`: also the step-time distribution, the cold-cache pass and the repeated regions (headline only)."""
     import numpy as np
@@ -247,7 +260,7 @@ def measure_config(cfg_index, args, steps, warmup, full):
         r.in_batch = batch.clone() if batch is not None else None
         r.run(r.in_pts, r.in_batch)
         r.status_sync()
-        r.stream = torch.cuda.Stream()
+        r.stream = replay_stream(torch, len(ring))
         ring.append(r)
     torch.cuda.synchronize()
     runner = ring[0]
@@ -276,7 +289,7 @@ def measure_config(cfg_index, args, steps, warmup, full):
     if use_graphs:
         for r in ring:
             with torch.cuda.stream(r.stream):
-                r.capture(r.in_pts, r.in_batch, overlapped=not args.serial)
+                r.capture(r.in_pts, r.in_batch, overlapped=args.branch_graphs and not args.serial)
         torch.cuda.synchronize()
 
     step_no = [0]
@@ -288,8 +301,8 @@ def measure_config(cfg_index, args, steps, warmup, full):
         with torch.cuda.stream(r.stream):
             if use_graphs and (tm is None or not tm.enabled):
                 r.replay()
-            elif args.serial:
-                r.run(r.in_pts, r.in_batch, tm)
+            elif args.serial or (use_graphs and not args.branch_graphs):
+                r.run(r.in_pts, r.in_batch, tm)          # the launch order the graph holds, issued from the host
             else:
                 r.run_overlapped(r.in_pts, r.in_batch, tm)
 
@@ -761,12 +774,15 @@ def main() -> int:
     ap.add_argument("--per-config", type=str, default="1,2,3,4", help="other configurations to list (comma separated; '' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one batch at a time, every call on one stream")
-    ap.add_argument("--frames-in-flight", type=int, default=3, choices=[1, 2, 3, 4],
+    ap.add_argument("--frames-in-flight", type=int, default=4, choices=[1, 2, 3, 4],
                     help="batches in flight: each has its own contexts, buffers and stream, so the small index / map kernels "
                          "of one batch fill the CUs that another batch's convs leave idle (a step is still one whole batch)")
-    ap.add_argument("--bracket-every", type=int, default=4,
+    ap.add_argument("--bracket-every", type=int, default=10,
                     help="the dominant kernel's launches carry event brackets on every N-th timed step (0 = never)")
     ap.add_argument("--no-graphs", action="store_true", help="issue every launch from the host instead of replaying HIP graphs")
+    ap.add_argument("--branch-graphs", action="store_true",
+                    help="one two-stream graph per branch (map building forked from the convs inside the graph) instead of one "
+                         "graph without forks per batch; measured slower: the batches in flight supply the overlap")
     ap.add_argument("--headline-only", action="store_true",
                     help="only the headline configuration's timed region and calibration: for profiler and counter runs")
     ap.add_argument("--dist-reps", type=int, default=200, help="single steps timed for the step-latency distribution")
@@ -786,6 +802,7 @@ def main() -> int:
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    replay_stream(torch, args.frames_in_flight - 1)      # the replay streams come first
 
     if args.copy_probe_mib > 0:
         src = torch.empty(args.copy_probe_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)

@@ -305,6 +305,7 @@ class ConfigRunner:
                 "valid": torch.empty((n_points,), dtype=torch.uint8, device=device),
             }
         self.graph = None
+        self.flat_graph = None
 
     def close(self) -> None:
         for ctx, _ in self.branches:
@@ -354,15 +355,29 @@ class ConfigRunner:
         configuration: a capture in which a forked stream forks again (branch stream -> its map stream) ended in a
         crash inside the runtime's end-of-capture on this ROCm, whereas a single level of forking is what the
         per-branch graphs have always used."""
-        for _, r in self.branches:
-            r.capture(points, batch, overlapped=overlapped)
         self.graph_points = points
+        if not overlapped:
+            # the whole pass in launch order on one stream: a graph without forks
+            side = torch.cuda.Stream(device=points.device)
+            side.wait_stream(torch.cuda.current_stream())
+            self.flat_graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self.flat_graph, stream=side):
+                self.graph_out = self.run(points, batch)
+            torch.cuda.current_stream().wait_stream(side)
+            self.graph = True
+            return
+        self.flat_graph = None
+        for _, r in self.branches:
+            r.capture(points, batch, overlapped=True)
         self.graph_out = [r.graph_out for _, r in self.branches]
         self.graph = True
 
     def replay(self) -> List[torch.Tensor]:
         """Replay the captured graphs: the first branch on the current stream, the others on streams of their own
         that fork from it and join it again (ordinary stream and event calls, outside any capture)."""
+        if self.flat_graph is not None:
+            self.flat_graph.replay()
+            return self.graph_out
         main = torch.cuda.current_stream()
         for bi, (_, r) in enumerate(self.branches[1:], start=1):
             s = self.side[bi - 1]

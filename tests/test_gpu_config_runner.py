@@ -86,4 +86,14 @@ def test_config_runner_every_way_of_running_matches_the_branches_alone(cfg_index
             outs = cr.replay()
         check(outs, f"replay {it}")
         check(cr.run_overlapped(frame, batch), f"eager after replay {it}")
+    progress("  capture (the whole pass as one graph without forks)")
+    with torch.cuda.stream(side):
+        cr.capture(frame, batch, overlapped=False)
+    torch.cuda.synchronize()
+    for it in range(3):
+        progress(f"  flat replay {it}")
+        with torch.cuda.stream(side):
+            outs = cr.replay()
+        check(outs, f"flat replay {it}")
+        check(cr.run(frame, batch), f"eager after flat replay {it}")
     cr.close()
