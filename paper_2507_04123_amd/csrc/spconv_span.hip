@@ -62,6 +62,7 @@ template <int CIN> struct SpanCfg {
 struct GroupInfo {
   int32_t lo, hi;
   bool span;
+  uint32_t rows;   // span mode: rows of the interval that hold data (0 for a group without a valid entry)
   unsigned long long valid[3];
 };
 
@@ -96,6 +97,7 @@ __device__ __forceinline__ GroupInfo analyze(const int32_t j[3]) {
   gi.lo = lo;
   gi.hi = hi;
   gi.span = bad == 0ull;
+  gi.rows = (gi.valid[0] | gi.valid[1] | gi.valid[2]) != 0ull ? width + 1u : 0u;
   return gi;
 }
 
@@ -145,7 +147,9 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   // loaded: rows past n_out are masked where the entries are used, never right after the load (that would
   // wait for the load at once)
   int32_t jq0[3], jq1[3], jq2[3];
-  u32x4 sreg[NI];           // gathered rows in flight
+  u32x4 sreg[NI];           // gathered rows in flight (an instruction that is skipped leaves its slot as it was)
+#pragma unroll
+  for (int i = 0; i < NI; ++i) sreg[i] = u32x4{0u, 0u, 0u, 0u};
   u32x4 wq[WPT];            // weights in flight
 
 #define EMC2_IDX_LOAD(GROUP, DST)                                                                          \
@@ -174,23 +178,31 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     const char* base_ = reinterpret_cast<const char*>(in) + (int64_t)(GI).lo * (CIN * 2);                  \
     const uint32_t last_ = (uint32_t)((GI).hi - (GI).lo);                                                  \
     _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                    \
-      const uint32_t p_ = (uint32_t)(i_ * RPI + srow);                                                     \
-      const uint32_t off_ = (p_ < last_ ? p_ : last_) * (uint32_t)(CIN * 2) + (uint32_t)(schunk * 16);     \
-      sreg[i_] = *reinterpret_cast<const u32x4*>(base_ + off_);                                            \
+      /* wave-uniform: an instruction none of whose rows holds data is not issued (its tile rows are never read) */ \
+      if ((uint32_t)(i_ * RPI) < (GI).rows) {                                                              \
+        const uint32_t p_ = (uint32_t)(i_ * RPI + srow);                                                   \
+        const uint32_t off_ = (p_ < last_ ? p_ : last_) * (uint32_t)(CIN * 2) + (uint32_t)(schunk * 16);   \
+        sreg[i_] = *reinterpret_cast<const u32x4*>(base_ + off_);                                          \
+      }                                                                                                    \
     }                                                                                                      \
   }
   // gather of exactly the rows one tap names: tile row p <- input row JROW[p] (absent entries re-read row 0)
 #define EMC2_GATHER_TAP(JROW)                                                                              \
   _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) {                                                      \
-    const int p_ = i_ * RPI + srow;                                                                        \
-    const int32_t j_ = __shfl((JROW), p_ & 63, 64);                                                        \
-    const int32_t r_ = (p_ < 64 && j_ >= 0) ? j_ : 0;                                                      \
-    sreg[i_] = *(reinterpret_cast<const u32x4*>(in + (int64_t)r_ * CIN) + schunk);                         \
+    if (i_ * RPI < 64) { /* compile time: a tap names 64 rows */                                           \
+      const int p_ = i_ * RPI + srow;                                                                      \
+      const int32_t j_ = __shfl((JROW), p_, 64);                                                           \
+      sreg[i_] = *(reinterpret_cast<const u32x4*>(in + (int64_t)(j_ >= 0 ? j_ : 0) * CIN) + schunk);       \
+    }                                                                                                      \
   }
 #define EMC2_GATHER_MAIN(GI, J)                                                                            \
   if ((GI).span) { EMC2_GATHER_SPAN(GI) } else { EMC2_GATHER_TAP((J)[0]) }
-#define EMC2_TILE_WRITE()                                                                                  \
-  _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_) my_tile[(i_ * RPI + srow) * ROW16 + schunk] = sreg[i_];
+  // registers -> tile, the first ROWS rows (wave-uniform; whole instructions)
+#define EMC2_TILE_WRITE_N(ROWS)                                                                            \
+  _Pragma("unroll") for (int i_ = 0; i_ < NI; ++i_)                                                        \
+    if ((uint32_t)(i_ * RPI) < (uint32_t)(ROWS)) my_tile[(i_ * RPI + srow) * ROW16 + schunk] = sreg[i_];
+  // ... what the main gather of group GI left in the registers: its interval, or the 64 rows of its first tap
+#define EMC2_TILE_WRITE(GI) EMC2_TILE_WRITE_N((GI).span ? (GI).rows : 64u)
   // one tap: lane l's LROW is the tile row that output row l of the wave reads.  The A operand of lane
   // (m, q) for tile mt is 16 bytes at piece 4*ks + q of tile row LROW[16*mt + m]: three lane-swap
   // instructions broadcast each 16-lane row of LROW to all four rows (no LDS round trip).
@@ -220,11 +232,11 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   {                                                                                                        \
     { const int32_t lrow_ = EMC2_LROW(0, C, GI); EMC2_TAP(0, lrow_, WB) }                                  \
     __builtin_amdgcn_wave_barrier();                                                                       \
-    if (!(GI).span) { EMC2_TILE_WRITE() EMC2_GATHER_TAP((C)[2]) }                                          \
+    if (!(GI).span) { EMC2_TILE_WRITE_N(64) EMC2_GATHER_TAP((C)[2]) }                                          \
     __builtin_amdgcn_wave_barrier();                                                                       \
     { const int32_t lrow_ = EMC2_LROW(1, C, GI); EMC2_TAP(1, lrow_, WB) }                                  \
     __builtin_amdgcn_wave_barrier();                                                                       \
-    if (!(GI).span) { EMC2_TILE_WRITE() EMC2_GATHER_MAIN(NXT, CNXT) }                                      \
+    if (!(GI).span) { EMC2_TILE_WRITE_N(64) EMC2_GATHER_MAIN(NXT, CNXT) }                                      \
     __builtin_amdgcn_wave_barrier();                                                                       \
     { const int32_t lrow_ = EMC2_LROW(2, C, GI); EMC2_TAP(2, lrow_, WB) }                                  \
   }
@@ -244,7 +256,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     EMC2_GATHER_MAIN(cur, c0)
     if constexpr (LATE) {
       // one interval ahead on the memory side: first pass of group 0 in the tile, next pass requested
-      EMC2_TILE_WRITE()
+      EMC2_TILE_WRITE(cur)
       EMC2_IDX_LOAD(2, jq2)
       EMC2_W_LOAD(1)
       if (cur.span) { EMC2_GATHER_MAIN(nxt, c1) } else { EMC2_GATHER_TAP(c0[1]) }
@@ -257,7 +269,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     EMC2_MASKED(c0, jq0)
     EMC2_MASKED(c1, jq1)
     if constexpr (!LATE) {
-      EMC2_TILE_WRITE()                       // rows of group g, requested during group g - 1
+      EMC2_TILE_WRITE(cur)                    // rows of group g, requested during group g - 1
       // requests: entries of group g + 2, weights of group g + 1, and the rows of the next pass (group
       // g + 1, or the second pass of this group if it runs in three passes)
       EMC2_IDX_LOAD(g + 2, jq2)
@@ -285,7 +297,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
       EMC2_MASKED(c2, jq2)                    // requested at the end of the previous group
       aft = analyze<SMAX>(c2);
       EMC2_W_STORE((g + 1) & 1)
-      EMC2_TILE_WRITE()                       // first pass of group g + 1
+      EMC2_TILE_WRITE(nxt)                    // first pass of group g + 1
       int32_t jn[3];
       EMC2_IDX_LOAD(g + 3, jn)
       EMC2_W_LOAD(g + 2)
@@ -317,6 +329,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 #undef EMC2_GATHER_TAP
 #undef EMC2_GATHER_MAIN
 #undef EMC2_TILE_WRITE
+#undef EMC2_TILE_WRITE_N
 #undef EMC2_TAP
 #undef EMC2_LROW
 #undef EMC2_COMPUTE
