@@ -230,6 +230,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
   // Only the memory operations of the (rare) three-pass mode are conditional inside a group.
 #define EMC2_COMPUTE(C, GI, NXT, CNXT, WB)                                                                 \
   {                                                                                                        \
+    __builtin_amdgcn_s_setprio(2);                                                                         \
     { const int32_t lrow_ = EMC2_LROW(0, C, GI); EMC2_TAP(0, lrow_, WB) }                                  \
     __builtin_amdgcn_wave_barrier();                                                                       \
     if (!(GI).span) { EMC2_TILE_WRITE_N(64) EMC2_GATHER_TAP((C)[2]) }                                          \
@@ -239,6 +240,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     if (!(GI).span) { EMC2_TILE_WRITE_N(64) EMC2_GATHER_MAIN(NXT, CNXT) }                                      \
     __builtin_amdgcn_wave_barrier();                                                                       \
     { const int32_t lrow_ = EMC2_LROW(2, C, GI); EMC2_TAP(2, lrow_, WB) }                                  \
+    __builtin_amdgcn_s_setprio(0);                                                                         \
   }
   // prologue.  The analyses of the groups (wave-uniform, ~80 scalar instructions each) are carried from
   // iteration to iteration, one new analysis per group, always of entries loaded a whole group earlier.
