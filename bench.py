@@ -774,7 +774,7 @@ def main() -> int:
     ap.add_argument("--per-config", type=str, default="1,2,3,4", help="other configurations to list (comma separated; '' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--serial", action="store_true", help="one batch at a time, every call on one stream")
-    ap.add_argument("--frames-in-flight", type=int, default=4, choices=[1, 2, 3, 4],
+    ap.add_argument("--frames-in-flight", type=int, default=4, choices=[1, 2, 3, 4, 5, 6, 8],
                     help="batches in flight: each has its own contexts, buffers and stream, so the small index / map kernels "
                          "of one batch fill the CUs that another batch's convs leave idle (a step is still one whole batch)")
     ap.add_argument("--bracket-every", type=int, default=10,
