@@ -203,6 +203,20 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
     if ((uint32_t)(i_ * RPI) < (uint32_t)(ROWS)) my_tile[(i_ * RPI + srow) * ROW16 + schunk] = sreg[i_];
   // ... what the main gather of group GI left in the registers: its interval, or the 64 rows of its first tap
 #define EMC2_TILE_WRITE(GI) EMC2_TILE_WRITE_N((GI).span ? (GI).rows : 64u)
+  // Issue order inside a tap (KS = 2, MT = NT = 4: 16 operand reads, 32 matrix instructions): operands are read one
+  // to two row tiles ahead of the matrix instructions that use them, so that after the first six reads of a tap a
+  // read's latency falls under the four matrix instructions before its use.
+#define EMC2_TAP_ORDER()                                                                                   \
+  if (KS == 2 && MT == 4 && NT == 4) {                                                                     \
+    __builtin_amdgcn_sched_group_barrier(0x100, 6, 0); /* b0..b3, a0, a1 of the first k-step */            \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0); __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  \
+    __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);                                                     \
+  }
   // one tap: lane l's LROW is the tile row that output row l of the wave reads.  The A operand of lane
   // (m, q) for tile mt is 16 bytes at piece 4*ks + q of tile row LROW[16*mt + m]: three lane-swap
   // instructions broadcast each 16-lane row of LROW to all four rows (no LDS round trip).
@@ -221,6 +235,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
       _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                    \
         _Pragma("unroll") for (int j = 0; j < NT; ++j) acc[mt][j] = MmaS<DT>::run(a[mt], b[j], acc[mt][j]); \
     }                                                                                                      \
+    EMC2_TAP_ORDER()                                                                                       \
   }
   // Tile row that output row `lane` reads at tap KX.  Span mode: entry minus lo.  Three-pass mode: the
   // tile holds exactly the rows of the tap being computed, row p for output row p.
@@ -333,6 +348,7 @@ __device__ __forceinline__ void span_wave(const uint16_t* __restrict__ in, const
 #undef EMC2_TILE_WRITE
 #undef EMC2_TILE_WRITE_N
 #undef EMC2_TAP
+#undef EMC2_TAP_ORDER
 #undef EMC2_LROW
 #undef EMC2_COMPUTE
   emc2_report_oob(oob, dev_flags);
