@@ -29,15 +29,16 @@ def assert_features_close(got: np.ndarray, exp: np.ndarray, rtol: float, what: s
                              f"got {got[i]!r} exp {exp[i]!r} rms {rms:.4g}")
 
 
-_PROGRESS_LOG = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out", "pytest_progress.log")
+_PROGRESS_LOG = os.environ.get("EMC2_PROGRESS_LOG", "")
 
 
 def progress(msg: str) -> None:
-    """A progress line of a long test: printed, and appended to a log file a job monitor can watch (pytest holds
-    back what a passing test prints)."""
+    """A progress line of a long test: printed, and appended to the file EMC2_PROGRESS_LOG names, if any, for a job
+    monitor to watch (pytest holds back what a passing test prints)."""
     print(msg, flush=True)
+    if not _PROGRESS_LOG:
+        return
     try:
-        os.makedirs(os.path.dirname(_PROGRESS_LOG), exist_ok=True)
         with open(_PROGRESS_LOG, "a") as f:
             f.write(msg + "\n")
     except OSError:
