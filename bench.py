@@ -15,6 +15,7 @@ import argparse
 import ctypes
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -286,11 +287,26 @@ def measure_config(cfg_index, args, steps, warmup, full):
     ctx0 = runner.branches[0][0]
 
     use_graphs = not args.no_graphs
+    # two-stage pipeline across batches: maps of the next batch under the convolutions of this one
+    can_stage = use_graphs and not args.serial and not args.branch_graphs and depth >= 2 and \
+        all(br.can_overlap for r in ring for _, br in r.branches)
+    want = args.launch_shape if can_stage else "batches"
+    if want == "auto":
+        # The staged form costs ~0.2 ms more host time per step (three graph launches and their events instead of
+        # one) and runs two or three streams instead of `depth`: it pays where a step is long and has several
+        # branches (config 5: +2 %), and loses on short steps (config 3: half the throughput).
+        want = "stages" if len(runner.branches) >= 2 and n_points >= 500_000 else "batches"
+    map_stream = replay_stream(torch, 0)
+    conv_streams = [replay_stream(torch, 1 + bi) for bi in range(len(runner.branches))]
     if use_graphs:
         for r in ring:
             with torch.cuda.stream(r.stream):
-                r.capture(r.in_pts, r.in_batch, overlapped=args.branch_graphs and not args.serial)
+                if want == "stages":
+                    r.capture_stages(r.in_pts, r.in_batch)
+                else:
+                    r.capture(r.in_pts, r.in_batch, overlapped=args.branch_graphs and not args.serial)
         torch.cuda.synchronize()
+    staged = want == "stages"
 
     step_no = [0]
 
@@ -298,6 +314,12 @@ def measure_config(cfg_index, args, steps, warmup, full):
         """One pass over one batch on the next runner of the ring; bracketed (eager) when `tm` is enabled."""
         r = ring[step_no[0] % depth]
         step_no[0] += 1
+        if staged:
+            if use_graphs and (tm is None or not tm.enabled):
+                r.replay_stages(map_stream, conv_streams)
+            else:
+                r.run_stages(r.in_pts, r.in_batch, map_stream, conv_streams, tm)
+            return
         with torch.cuda.stream(r.stream):
             if use_graphs and (tm is None or not tm.enabled):
                 r.replay()
@@ -310,6 +332,14 @@ def measure_config(cfg_index, args, steps, warmup, full):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if args.config_result_only:
+        # a child process measuring one of the small configurations starts on an idle GPU and its whole timed region
+        # lasts a millisecond or two: keep stepping (untimed) until the clocks have come up
+        t_w = time.perf_counter()
+        while time.perf_counter() - t_w < 0.05:
+            for _ in range(depth):
+                step()
+            torch.cuda.synchronize()
 
     # Calibration pass (outside the timed region): one stream, one batch at a time, every library call bracketed.
     # Finds the dominant conv kernel, gives its launch duration with the GPU to itself, and the per-stage breakdown.
@@ -428,6 +458,9 @@ def measure_config(cfg_index, args, steps, warmup, full):
                     + (f"; image gather {cfg.camera.height}x{cfg.camera.width}x{cfg.camera.channels}" if cfg.camera else ""),
         "value": frames_per_s, "unit": "frames/s", "ms_per_step": ms_per_step, "steps": steps,
         "host_issue_ms_per_step": issue * 1e3 / steps, "dtype": DTYPE_NAME[cfg.dtype],
+        "launch_shape": ("two-stage pipeline across batches: maps of the next batch under the convs of this one"
+                         if staged else "one batch at a time" if depth == 1 else "independent batches, one stream each"),
+
         "voxels_per_level": {br.branch.name: vox[bi] for bi, (_, br) in enumerate(runner.branches)},
         "roofline": roofline,
         "stages_ms_calibration_pass": stage_ms,
@@ -453,17 +486,29 @@ def measure_config(cfg_index, args, steps, warmup, full):
         # one batch at a time: latency of a step, start to end, over many single steps
         lat = []
         r0 = ring[0]
-        with torch.cuda.stream(r0.stream):
+        if staged:
+            # one step alone in the staged form: from the first map kernel to the last branch's last convolution
             for _ in range(args.dist_reps):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                if use_graphs:
-                    r0.replay()
-                else:
-                    r0.run_overlapped(r0.in_pts, r0.in_batch)
-                e1.record()
+                e0.record(map_stream)
+                r0.replay_stages(map_stream, conv_streams)
+                for ev in r0.ev_convs:
+                    map_stream.wait_event(ev)
+                e1.record(map_stream)
                 e1.synchronize()
                 lat.append(e0.elapsed_time(e1))
+        else:
+            with torch.cuda.stream(r0.stream):
+                for _ in range(args.dist_reps):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    if use_graphs:
+                        r0.replay()
+                    else:
+                        r0.run_overlapped(r0.in_pts, r0.in_batch)
+                    e1.record()
+                    e1.synchronize()
+                    lat.append(e0.elapsed_time(e1))
         res["step_latency_ms"] = percentiles(lat)
         # cold inputs: every step reads another of `cold_frames` distinct seeded frames (copied into the runner's
         # input buffer on its stream right before the pass), so no step finds its own input or intermediate data
@@ -475,14 +520,14 @@ def measure_config(cfg_index, args, steps, warmup, full):
             cold.append(torch.from_numpy(p_).cuda())
         for i in range(depth + 2):
             r = ring[i % depth]
-            with torch.cuda.stream(r.stream):
+            with torch.cuda.stream(map_stream if staged else r.stream):
                 r.in_pts.copy_(cold[i % n_cold], non_blocking=True)
             step()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for i in range(steps * 2):
             r = ring[step_no[0] % depth]
-            with torch.cuda.stream(r.stream):
+            with torch.cuda.stream(map_stream if staged else r.stream):
                 r.in_pts.copy_(cold[i % n_cold], non_blocking=True)
             step()
         torch.cuda.synchronize()
@@ -765,6 +810,34 @@ def guarded(fn, *a):
         return {"error": repr(exc)}
 
 
+def measure_other_configs(args):
+    """The `per_config` list: each of the other configurations measured by a child process of its own (`bench.py
+    --config N`, run to its end before the next starts, and before this process touches the GPU), so that its figures
+    do not depend on what the headline measurement created before it: torch hands streams out of a small round-robin
+    pool, streams share a few hardware queues, and a second process with work on the GPU slows a launch-bound one."""
+    per = []
+    for idx in [int(x) for x in args.per_config.split(",") if x.strip()]:
+        if idx == args.config:
+            continue
+        cmd = [sys.executable, os.path.abspath(__file__), "--config", str(idx), "--config-result-only",
+               "--steps", str(min(args.steps, 20)), "--warmup", str(args.warmup),
+               "--frames-in-flight", str(args.frames_in_flight), "--bracket-every", str(args.bracket_every),
+               "--launch-shape", args.launch_shape]
+        for flag, on in (("--no-cpu-baseline", args.no_cpu_baseline), ("--no-graphs", args.no_graphs),
+                         ("--branch-graphs", args.branch_graphs), ("--serial", args.serial)):
+            if on:
+                cmd.append(flag)
+        try:
+            cp = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, timeout=600, check=False)
+            line = cp.stdout.decode().strip().splitlines()[-1] if cp.stdout.strip() else ""
+            if cp.returncode != 0 or not line.startswith("{"):
+                raise RuntimeError(f"exit {cp.returncode}: {cp.stderr.decode()[-400:]}")
+            per.append(json.loads(line))
+        except Exception as exc:  # noqa: BLE001
+            per.append({"config": idx, "error": repr(exc)})
+    return per
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -783,6 +856,12 @@ def main() -> int:
     ap.add_argument("--branch-graphs", action="store_true",
                     help="one two-stream graph per branch (map building forked from the convs inside the graph) instead of one "
                          "graph without forks per batch; measured slower: the batches in flight supply the overlap")
+    ap.add_argument("--launch-shape", choices=["auto", "batches", "stages"], default="auto",
+                    help="batches: every batch in flight replays its whole pass (one graph) on a stream of its own; "
+                         "stages: a two-stage pipeline, voxelization and kernel maps of the next batch on a map stream "
+                         "under the convolutions of this batch on one conv stream per branch; auto: stages for a "
+                         "workload with several branches and at least 500 000 points per step, else batches")
+    ap.add_argument("--config-result-only", action="store_true", help=argparse.SUPPRESS)
     ap.add_argument("--headline-only", action="store_true",
                     help="only the headline configuration's timed region and calibration: for profiler and counter runs")
     ap.add_argument("--dist-reps", type=int, default=200, help="single steps timed for the step-latency distribution")
@@ -796,6 +875,8 @@ def main() -> int:
         print("bench.py measures one GPU only: this build has no multi-GPU path (frames shard across GPUs with no "
               "exchange, so several GPUs would each run this same program on their share). Run with --gpus 1.", file=sys.stderr)
         return 2
+
+    per = measure_other_configs(args) if not (args.headline_only or args.config_result_only) else None
 
     import faulthandler
     faulthandler.enable()            # a fatal signal in native code still names the Python line it came from
@@ -811,6 +892,17 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    if args.config_result_only:
+        # child of a full run: one configuration's entry of `per_config`, as one JSON line
+        r_, ring_, (cfg_, p_, b_) = measure_config(args.config, args, args.steps, args.warmup, full=False)
+        for x in ring_:
+            x.close()
+        if not args.no_cpu_baseline:
+            import oracle
+            r_["cpu_baseline"] = cpu_baseline(cfg_, p_, b_, min(oracle.max_threads(), 16), single_thread_sample=False)
+        print(json.dumps(r_))
+        return 0
+
     head, ring, (cfg, pts_np, batch_np) = measure_config(args.config, args, args.steps, args.warmup, full=not args.headline_only)
     for r in ring:
         r.close()
@@ -822,7 +914,7 @@ def main() -> int:
         "value": head["value"], "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
-        "config": {"workload": head["workload"], "frames_per_step": cfg.n_frames, "batches_in_flight": 1 if args.serial else args.frames_in_flight,
+        "config": {"workload": head["workload"], "frames_per_step": cfg.n_frames, "batches_in_flight": 1 if args.serial else args.frames_in_flight, "launch_shape": head["launch_shape"],
                    "hip_graphs": not args.no_graphs, "voxels_per_level": head["voxels_per_level"]},
         "roofline": head["roofline"],
     }
@@ -834,23 +926,6 @@ def main() -> int:
 
     if not args.headline_only:
         out["measured_ceilings"] = guarded(measure_probes, torch)
-        per = []
-        import oracle
-        threads = min(oracle.max_threads(), 16)
-        for idx in [int(x) for x in args.per_config.split(",") if x.strip()]:
-            if idx == args.config:
-                continue
-            try:
-                r_, ring_, (cfg_, p_, b_) = measure_config(idx, args, min(args.steps, 20), args.warmup, full=False)
-                for x in ring_:
-                    x.close()
-                del ring_
-                torch.cuda.empty_cache()
-                if not args.no_cpu_baseline:
-                    r_["cpu_baseline"] = cpu_baseline(cfg_, p_, b_, threads, single_thread_sample=False)
-                per.append(r_)
-            except Exception as exc:  # noqa: BLE001
-                per.append({"config": idx, "error": repr(exc)})
         out["per_config"] = per
         out["project_gather"] = guarded(side_project_gather, torch)
         dq = guarded(side_decoder, torch)

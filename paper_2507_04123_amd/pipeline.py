@@ -74,6 +74,12 @@ class Level:
     down_nbr: Optional[torch.Tensor] = None   # map from the previous level into this one
 
 
+def capture_stream(device) -> "torch.cuda.Stream":
+    """A stream to record one graph capture on: a stream of its own for every capture.  Graphs recorded on one shared
+    stream were measured 8-17 % slower when several of them are replayed side by side on different streams."""
+    return torch.cuda.Stream(device=device)
+
+
 class BranchRunner:
     """Runs one Branch (one voxelization + its conv stack) through the library."""
 
@@ -125,13 +131,20 @@ class BranchRunner:
         # Second stream for voxelization and kernel maps.  They share the context's scratch and stay ordered
         # among themselves; the convolutions (packed weights: no context scratch) run on the caller's stream
         # and wait, per layer, only for the map they read.  Both streams keep the default priority.
-        self.map_stream = torch.cuda.Stream(device=device)
+        self._map_stream = None       # created on first use: torch hands streams out of a small round-robin pool
+        self._device = device
         self.ev_feats = torch.cuda.Event()
         self.ev_done = None           # recorded on the caller's stream at the end of the previous overlapped run
         self.ev_subm = [torch.cuda.Event() for _ in self.levels]
         self.ev_down = [torch.cuda.Event() for _ in self.levels]
         self.can_overlap = all(lay == B.W_PACKED or not ctx.uses_mfma(dtype, l.cin, l.cout)
                                for (_, lay), l in zip(self.wdev, branch.layers))
+
+    @property
+    def map_stream(self) -> "torch.cuda.Stream":
+        if self._map_stream is None:
+            self._map_stream = torch.cuda.Stream(device=self._device)
+        return self._map_stream
 
     def run_overlapped(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None,
                        inputs_ready: Optional["torch.cuda.Event"] = None, _capturing: bool = False) -> torch.Tensor:
@@ -207,7 +220,7 @@ class BranchRunner:
         ~50 small launches, and issuing them from the host one by one costs about as long as the GPU needs to run
         them.  The graph reads `points` / `batch` and writes this runner's buffers, as run() does; replay it with
         graph.replay() on any stream.  The library records no memset node (every clear is a kernel)."""
-        side = torch.cuda.Stream(device=points.device)
+        side = capture_stream(points.device)
         side.wait_stream(torch.cuda.current_stream())
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
@@ -246,6 +259,58 @@ class BranchRunner:
                         ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n,
                                        in_slot=lv.slot)
                     built[lvl] = True
+                nbr = lv.subm_nbr
+            y = self.acts[li]
+            with tm(("conv", li)):
+                ctx.spconv(self.dtype, x, self.wdev[li][0], p["scale"] if has_epi else None,
+                           p["shift"] if has_epi else None, layer.epilogue, nbr, lv.n, lv.cap, y,
+                           w_layout=self.wdev[li][1], map_hint=layer.kind)
+            x = y
+        return x
+
+    def run_maps(self, points: torch.Tensor, batch: Optional[torch.Tensor], timer=None) -> None:
+        """First stage of a pass, on the current stream: voxelization and every kernel map of the branch (all the
+        work that uses the context's scratch).  run_convs() is the second stage; together they do what run() does,
+        with every map built before the first convolution."""
+        ctx, br = self.ctx, self.branch
+        tm = timer if timer is not None else _no_timer
+        l0 = self.levels[0]
+        with tm("voxelize"):
+            ctx.voxelize(points, batch, br.spec, l0.cap, l0.coords, self.feats32, self.counts, l0.n,
+                         feats_lp=self.feats_lp, index_slot=l0.slot)
+        lvl = 0
+        built = [False] * len(self.levels)
+        nb = br.spec.n_batch
+        for layer in br.layers:
+            if layer.kind == STRIDED:
+                src, dst = self.levels[lvl], self.levels[lvl + 1]
+                with tm("kmap_strided"):
+                    ctx.build_kmap(B.STRIDED, src.coords, src.n, src.cap, src.grid, nb, dst.cap, dst.down_nbr, dst.n,
+                                   out_coords=dst.coords, in_slot=src.slot, out_slot=dst.slot)
+                lvl += 1
+            elif not built[lvl]:
+                lv = self.levels[lvl]
+                with tm("kmap_subm"):
+                    ctx.build_kmap(B.SUBM, lv.coords, lv.n, lv.cap, lv.grid, nb, lv.cap, lv.subm_nbr, lv.n, in_slot=lv.slot)
+                built[lvl] = True
+
+    def run_convs(self, timer=None) -> torch.Tensor:
+        """Second stage of a pass, on the current stream: every convolution of the branch over the voxels and kernel
+        maps run_maps() left in this runner's buffers.  Uses no context scratch when the weights are packed, so it
+        may overlap the first stage of another runner."""
+        ctx, br = self.ctx, self.branch
+        tm = timer if timer is not None else _no_timer
+        x = self.feats32 if self.dtype == F32 else self.feats_lp
+        lvl = 0
+        for li, layer in enumerate(br.layers):
+            p = self.params[li]
+            has_epi = layer.epilogue != EPI_NONE
+            if layer.kind == STRIDED:
+                lvl += 1
+                lv = self.levels[lvl]
+                nbr = lv.down_nbr
+            else:
+                lv = self.levels[lvl]
                 nbr = lv.subm_nbr
             y = self.acts[li]
             with tm(("conv", li)):
@@ -294,7 +359,8 @@ class ConfigRunner:
             seed = gen.frame_seed(cfg.index, 0) + len(br.name)
             self.branches.append((ctx, BranchRunner(ctx, br, cfg.dtype, n_points, device_params(br.layers, seed, cfg.dtype),
                                                     capacities=caps, device=device)))
-        self.side = [torch.cuda.Stream(device=device) for _ in self.branches[1:]]
+        self._side: List["torch.cuda.Stream"] = []
+        self._device = device
         self.camera = None
         if cfg.camera is not None:
             cam, seed = cfg.camera, gen.frame_seed(cfg.index, 0)
@@ -306,6 +372,9 @@ class ConfigRunner:
             }
         self.graph = None
         self.flat_graph = None
+        self.ev_maps = torch.cuda.Event()
+        self.ev_convs = [torch.cuda.Event() for _ in self.branches]
+        self.stages_in_flight = False
 
     def close(self) -> None:
         for ctx, _ in self.branches:
@@ -314,6 +383,13 @@ class ConfigRunner:
     def status_sync(self) -> None:
         for ctx, _ in self.branches:
             ctx.status_sync()
+
+    @property
+    def side(self) -> List["torch.cuda.Stream"]:
+        """Streams of the branches after the first when branches run side by side (created on first use)."""
+        if not self._side:
+            self._side = [torch.cuda.Stream(device=self._device) for _ in self.branches[1:]]
+        return self._side
 
     def _gather(self, points: torch.Tensor, tm) -> None:
         if self.camera is not None:
@@ -358,7 +434,7 @@ class ConfigRunner:
         self.graph_points = points
         if not overlapped:
             # the whole pass in launch order on one stream: a graph without forks
-            side = torch.cuda.Stream(device=points.device)
+            side = capture_stream(points.device)
             side.wait_stream(torch.cuda.current_stream())
             self.flat_graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(self.flat_graph, stream=side):
@@ -371,6 +447,76 @@ class ConfigRunner:
             r.capture(points, batch, overlapped=True)
         self.graph_out = [r.graph_out for _, r in self.branches]
         self.graph = True
+
+    def capture_stages(self, points: torch.Tensor, batch: Optional[torch.Tensor]) -> None:
+        """The pass as two stages, for pipelining across batches: one fork-free graph with every branch's
+        voxelization and kernel maps (and the point-to-image gather), and one fork-free graph per branch with its
+        convolutions.  replay_stages() launches them on a map stream and on one conv stream per branch, so that the
+        first stage of the next batch (another runner, another context) runs under the convolutions of this one."""
+        assert all(r.can_overlap for _, r in self.branches), "the conv stage must not use context scratch"
+        cur = torch.cuda.current_stream()
+
+        def grab(fn):
+            side = capture_stream(points.device)
+            side.wait_stream(cur)
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                out = fn()
+            cur.wait_stream(side)
+            return g, out
+
+        def maps():
+            for _, r in self.branches:
+                r.run_maps(points, batch)
+            self._gather(points, _no_timer)
+
+        self.stage_maps, _ = grab(maps)
+        self.stage_convs, self.graph_out = [], []
+        for _, r in self.branches:
+            g, out = grab(r.run_convs)
+            self.stage_convs.append(g)
+            self.graph_out.append(out)
+        self.graph_points = points
+
+    def replay_stages(self, map_stream: "torch.cuda.Stream", conv_streams: Sequence["torch.cuda.Stream"]) -> List[torch.Tensor]:
+        """One pass from the staged graphs.  The maps wait for this runner's previous convolutions (they rewrite what
+        those read); each branch's convolutions wait for the maps."""
+        if self.stages_in_flight:
+            for ev in self.ev_convs:
+                map_stream.wait_event(ev)
+        with torch.cuda.stream(map_stream):
+            self.stage_maps.replay()
+            self.ev_maps.record(map_stream)
+        for bi, g in enumerate(self.stage_convs):
+            cs = conv_streams[bi % len(conv_streams)]
+            cs.wait_event(self.ev_maps)
+            with torch.cuda.stream(cs):
+                g.replay()
+                self.ev_convs[bi].record(cs)
+        self.stages_in_flight = True
+        return self.graph_out
+
+    def run_stages(self, points: torch.Tensor, batch: Optional[torch.Tensor], map_stream: "torch.cuda.Stream",
+                   conv_streams: Sequence["torch.cuda.Stream"], timer=None) -> List[torch.Tensor]:
+        """replay_stages() issued from the host, call by call (same streams, same events; `timer` brackets the calls)."""
+        tm = timer if timer is not None else _no_timer
+        if self.stages_in_flight:
+            for ev in self.ev_convs:
+                map_stream.wait_event(ev)
+        with torch.cuda.stream(map_stream):
+            for bi, (_, r) in enumerate(self.branches):
+                r.run_maps(points, batch, (lambda tag, bi=bi: tm((bi, tag))) if timer is not None else None)
+            self._gather(points, tm)
+            self.ev_maps.record(map_stream)
+        outs = []
+        for bi, (_, r) in enumerate(self.branches):
+            cs = conv_streams[bi % len(conv_streams)]
+            cs.wait_event(self.ev_maps)
+            with torch.cuda.stream(cs):
+                outs.append(r.run_convs((lambda tag, bi=bi: tm((bi, tag))) if timer is not None else None))
+                self.ev_convs[bi].record(cs)
+        self.stages_in_flight = True
+        return outs
 
     def replay(self) -> List[torch.Tensor]:
         """Replay the captured graphs: the first branch on the current stream, the others on streams of their own

@@ -96,4 +96,17 @@ def test_config_runner_every_way_of_running_matches_the_branches_alone(cfg_index
             outs = cr.replay()
         check(outs, f"flat replay {it}")
         check(cr.run(frame, batch), f"eager after flat replay {it}")
+    progress("  capture (two stages: maps on one stream, each branch's convolutions on another)")
+    with torch.cuda.stream(side):
+        cr.capture_stages(frame, batch)
+    torch.cuda.synchronize()
+    map_stream = torch.cuda.Stream()
+    conv_streams = [torch.cuda.Stream() for _ in cr.branches]
+    for it in range(3):
+        progress(f"  staged replay {it}")
+        outs = cr.replay_stages(map_stream, conv_streams)
+        outs = cr.replay_stages(map_stream, conv_streams)     # back to back: the maps wait for the previous convolutions
+        check(outs, f"staged replay {it}")
+        check(cr.run_stages(frame, batch, map_stream, conv_streams), f"staged eager issue after replay {it}")
+        check(cr.run(frame, batch), f"eager after staged replay {it}")
     cr.close()
