@@ -81,6 +81,9 @@ template <int CIN, int COUT> struct DirectCfg {
   static constexpr int MT = (CIN <= 32 && COUT <= 32) ? 4 : 2;
   // waves per SIMD the register allocator must leave room for (the 128-channel shapes keep 64-128 accumulators
   // and as many operands in flight)
+  // (128 -> 128 ends up at one wave per SIMD whatever is asked for here -- 83 KB of LDS, 360 registers -- and the
+  // compiler says so in a warning; asking for one outright, or forcing two with a shorter weight prefetch, were
+  // both measured slower)
   static constexpr int MINW = (CIN >= 128 || COUT >= 128) ? 2 : 3;
 };
 
