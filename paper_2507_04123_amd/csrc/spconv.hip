@@ -175,7 +175,7 @@ template <> struct Mma4<EMC2_BF16> {
 };
 
 template <int DT, int CIN, int COUT>
-__global__ void __launch_bounds__(256) k_spconv_rows(const uint16_t* __restrict__ in, const uint16_t* __restrict__ w,
+__global__ void __launch_bounds__(256, 4) k_spconv_rows(const uint16_t* __restrict__ in, const uint16_t* __restrict__ w,
                                                      const float* __restrict__ scale, const float* __restrict__ shift,
                                                      int epilogue, const int32_t* __restrict__ nbr,
                                                      const int32_t* __restrict__ d_n_out, int64_t capacity_out,
