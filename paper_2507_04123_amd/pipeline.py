@@ -569,6 +569,23 @@ class RoutedRunner:
         for ctx, _ in self.runners:
             ctx.status_sync()
 
+    def capture(self, points: torch.Tensor, scene: torch.Tensor, props: torch.Tensor, prop_scene: Optional[torch.Tensor],
+                dist: float, conf: float) -> None:
+        """Record one routed pass (dispatch, grouping, every expert's stack) as one fork-free HIP graph.  The graph reads
+        the four input tensors in place: new proposals, scene ids and points are written into them before replay();
+        their sizes (number of proposals included) and the two thresholds are those of the capture."""
+        cur = torch.cuda.current_stream()
+        side = capture_stream(points.device)
+        side.wait_stream(cur)
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph, stream=side):
+            self.graph_out = self.run(points, scene, props, prop_scene, dist, conf)
+        cur.wait_stream(side)
+
+    def replay(self) -> List[torch.Tensor]:
+        self.graph.replay()
+        return self.graph_out
+
     def run(self, points: torch.Tensor, scene: torch.Tensor, props: torch.Tensor, prop_scene: Optional[torch.Tensor],
             dist: float, conf: float) -> List[torch.Tensor]:
         ctx0 = self.runners[0][0]

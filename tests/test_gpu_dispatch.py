@@ -175,3 +175,72 @@ def test_routed_runner_matches_the_ungrouped_run_scene_by_scene():
                 assert_features_close(fg[sg[k]:eg[k]], fr[sr[s]:er[s]], 2e-2, f"expert {e} layer {li} scene {s}: features")
         ctx.close()
     rr.close()
+
+
+def test_routed_runner_graph_replays_follow_their_inputs():
+    """One routed pass recorded as a HIP graph and replayed on changing proposals and points (written into the captured
+    tensors in place): every replay routes the scenes as the oracle does for the inputs of that replay and leaves the
+    same voxels, maps and features as the same pass issued from the host, with eager work between the replays."""
+    from helpers import assert_features_close, progress
+    from paper_2507_04123_amd.configs import get_config, expert_branches
+    from paper_2507_04123_amd.pipeline import RoutedRunner
+    cfg = get_config(5)
+    n_scenes = cfg.n_frames
+    n_props = 600
+    frames = [gen.make_frames(cfg, first_frame=8 * k) for k in range(3)]
+    prop_sets = []
+    for k in range(3):
+        p_np, s_np = gen.make_proposals(n_scenes, 21 + k)
+        idx = np.resize(np.arange(len(p_np)), n_props)          # the captured proposal count is fixed: repeat to fill
+        prop_sets.append((p_np[idx].copy(), s_np[idx].copy()))
+    pts = torch.from_numpy(frames[0][0]).cuda()
+    scene = torch.from_numpy(frames[0][1]).cuda()
+    props = torch.from_numpy(prop_sets[0][0]).cuda()
+    pscene = torch.from_numpy(prop_sets[0][1]).cuda()
+    experts = expert_branches(n_scenes)
+    seed = gen.frame_seed(5, 0)
+    rr = RoutedRunner(experts, cfg.dtype, pts.shape[0], n_scenes, seed)
+    ref = RoutedRunner(experts, cfg.dtype, pts.shape[0], n_scenes, seed)
+    rr.run(pts, scene, props, pscene, 23.5, 0.5)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        rr.capture(pts, scene, props, pscene, 23.5, 0.5)
+    torch.cuda.synchronize()
+    seen = set()
+    for it in range(5):
+        k = it % 3
+        pts.copy_(torch.from_numpy(frames[k][0]))
+        scene.copy_(torch.from_numpy(frames[k][1]))
+        props.copy_(torch.from_numpy(prop_sets[k][0]))
+        pscene.copy_(torch.from_numpy(prop_sets[k][1]))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            outs = rr.replay()
+        torch.cuda.synchronize()
+        rr.status_sync()
+        e_np, c_np, o_np = oracle.dispatch(prop_sets[k][0], prop_sets[k][1], n_scenes, 23.5, 0.5)
+        assert np.array_equal(rr.expert.cpu().numpy(), e_np) and np.array_equal(rr.counts.cpu().numpy(), c_np)
+        assert np.array_equal(rr.order.cpu().numpy(), o_np)
+        seen.add(tuple(c_np.tolist()))
+        progress(f"routed replay {it}: scenes per expert {c_np.tolist()}")
+        exp_outs = ref.run(pts, scene, props, pscene, 23.5, 0.5)      # the same pass issued from the host (eager work between replays)
+        torch.cuda.synchronize()
+        ref.status_sync()
+        for e, ((_, g), (_, h)) in enumerate(zip(rr.runners, ref.runners)):
+            for lg, lh in zip(g.levels, h.levels):
+                n = int(lh.n.item())
+                assert int(lg.n.item()) == n
+                assert torch.equal(lg.coords[:n], lh.coords[:n])
+            for li in range(len(g.branch.layers)):
+                mg, lvg = g.layer_map(li)
+                mh, lvh = h.layer_map(li)
+                n = int(lvh.n.item())
+                assert torch.equal(mg[:, :n], mh[:, :n]), f"replay {it} expert {e} layer {li}: kernel map"
+            n = int(h.levels[-1].n.item())
+            if n:
+                assert_features_close(outs[e][:n].float().cpu().numpy(), exp_outs[e][:n].float().cpu().numpy(), 2e-2,
+                                      f"replay {it} expert {e} features")
+    assert len(seen) >= 2, "the proposal sets should route the scenes differently"
+    rr.close()
+    ref.close()
